@@ -1,0 +1,337 @@
+"""CPU oracle for prefix-shared DPO attention (forward, backward, block mask).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, fp64 statement of what
+the library computes.  Only the tests, the smoke check and the benchmark's
+`cpu_baseline` leg may import it; the product path never does.  It shares no
+code with the HIP path and does not import it.
+
+What it follows:
+  * the prefix-sharing mask (Algorithm 1) and its packed form (Algorithm 3),
+    evaluated literally as three boolean clauses from materialised per-token
+    arrays I_chosen, I_rejected (completion start indices) and D (document ids);
+  * the baseline packing mask of Algorithm 2 (per-token response ids R);
+  * ordinary softmax attention on the allowed pairs (Section 3.1 states that
+    nothing else changes), with the textbook explicit backward;
+  * the per-mini-batch block mask of Section 3.1 (blocks with no allowed pair are
+    skipped), as a brute-force classification over the dense boolean mask.
+
+Readings where the paper is silent (all restated where they are used):
+  - start indices are row-absolute positions (they are compared with q and kv);
+  - padding tokens belong to no document: they are never keys, their query row
+    is empty, and every output at a padding position is exactly zero
+    (LSE = -inf);
+  - grouped-query heads: q-heads [g*G, (g+1)*G) use kv-head g;
+  - the softmax scale is a parameter; LSE is the natural log of the sum of
+    exp(scaled scores).
+
+Arithmetic is float64 throughout.  A matmul, max, exp, sum and log are the only
+library steps; there is no tiling or fusion, each sample's block is dense.
+
+Parity pins (see tests/test_oracle_*.py): explicit set description of the mask,
+closed-form pair counts and the paper's two ideal-speedup footnotes, pure-Python
+brute force, torch fp64 scaled_dot_product_attention (+autograd), finite
+differences, the no-contamination invariant against plain causal attention on
+[prompt|chosen] and [prompt|rejected], packing independence, response swap
+symmetry, GQA expansion.  No function here is unpinned.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+SKIPPED, PARTIAL, FULL = 0, 1, 2
+PAD_DOC = -1
+PAD_START = np.iinfo(np.int32).max
+
+
+# --------------------------------------------------------------------------
+# per-token arrays (the inputs of Algorithm 3)
+# --------------------------------------------------------------------------
+def index_arrays(offset, prefix_len, chosen_len, rejected_len, total_tokens):
+    """Materialise I_chosen, I_rejected, D for a flat buffer of total_tokens.
+
+    Every token of document i stores that document's chosen start
+    offset+prefix and rejected start offset+prefix+chosen (Algorithm 3 reads
+    them at the query position).  Padding gets D = -1 and zero indices.
+    """
+    T = int(total_tokens)
+    I_chosen = np.zeros(T, dtype=np.int64)
+    I_rejected = np.zeros(T, dtype=np.int64)
+    D = np.full(T, PAD_DOC, dtype=np.int64)
+    for i in range(len(offset)):
+        o, p, c, r = int(offset[i]), int(prefix_len[i]), int(chosen_len[i]), int(rejected_len[i])
+        n = p + c + r
+        if o < 0 or p < 0 or c < 0 or r < 0 or o + n > T:
+            raise ValueError("sample %d out of range" % i)
+        if np.any(D[o:o + n] != PAD_DOC):
+            raise ValueError("sample %d overlaps another" % i)
+        D[o:o + n] = i
+        I_chosen[o:o + n] = o + p
+        I_rejected[o:o + n] = o + p + c
+    return I_chosen, I_rejected, D
+
+
+def response_ids(offset, prefix_len, chosen_len, rejected_len, total_tokens):
+    """Per-token response ids R of Algorithm 2 for the paired format, in which
+    each document is one [prompt | response] unit (chosen_len = rejected_len = 0
+    in this library's sample table)."""
+    T = int(total_tokens)
+    R = np.full(T, PAD_DOC, dtype=np.int64)
+    for i in range(len(offset)):
+        n = int(prefix_len[i]) + int(chosen_len[i]) + int(rejected_len[i])
+        R[int(offset[i]):int(offset[i]) + n] = i
+    return R
+
+
+# --------------------------------------------------------------------------
+# masks
+# --------------------------------------------------------------------------
+def prefix_sharing_mask(q, kv, chosen_ind, rejected_ind):
+    """Algorithm 1 for one sample: q, kv broadcastable integer arrays."""
+    causal_mask = kv <= q
+    dpo_mask = ~((rejected_ind <= q) & (chosen_ind <= kv) & (kv < rejected_ind))
+    return causal_mask & dpo_mask
+
+
+def packed_prefix_sharing_mask(q, kv, I_chosen, I_rejected, D):
+    """Algorithm 3 over the flat buffer.  q, kv: broadcastable integer arrays."""
+    causal_mask = kv <= q
+    # padding is in no document, so it matches nothing, itself included
+    document_mask = (D[q] == D[kv]) & (D[q] != PAD_DOC)
+    chosen_ind = I_chosen[q]
+    rejected_ind = I_rejected[q]
+    dpo_mask = ~((rejected_ind <= q) & (chosen_ind <= kv) & (kv < rejected_ind))
+    return causal_mask & document_mask & dpo_mask
+
+
+def response_id_mask(q, kv, R):
+    """Algorithm 2 (packing without prefix sharing)."""
+    causal_mask = kv <= q
+    response_mask = (R[q] == R[kv]) & (R[q] != PAD_DOC)
+    return causal_mask & response_mask
+
+
+def dense_mask(I_chosen, I_rejected, D, q_lo=0, q_hi=None, k_lo=0, k_hi=None):
+    """Boolean matrix allowed[q - q_lo, kv - k_lo] of Algorithm 3."""
+    T = D.shape[0]
+    q_hi = T if q_hi is None else q_hi
+    k_hi = T if k_hi is None else k_hi
+    q = np.arange(q_lo, q_hi, dtype=np.int64)[:, None]
+    kv = np.arange(k_lo, k_hi, dtype=np.int64)[None, :]
+    return packed_prefix_sharing_mask(q, kv, I_chosen, I_rejected, D)
+
+
+def count_allowed(I_chosen, I_rejected, D, stripe=256):
+    """Number of allowed (q, kv) pairs, counted on the dense mask stripe by stripe."""
+    T = D.shape[0]
+    total = 0
+    for q_lo in range(0, T, stripe):
+        q_hi = min(T, q_lo + stripe)
+        total += int(dense_mask(I_chosen, I_rejected, D, q_lo, q_hi, 0, q_hi).sum())
+    return total
+
+
+# --------------------------------------------------------------------------
+# block mask (Section 3.1: computed once per mini-batch, blocks with no allowed
+# pair are skipped)
+# --------------------------------------------------------------------------
+def classify_tiles(I_chosen, I_rejected, D, tile_q, tile_k):
+    """Brute-force class of every (q-tile, k-tile) of the global grid.
+
+    Tile t covers tokens [t*tile, min((t+1)*tile, T)).  SKIPPED: no allowed
+    pair.  FULL: the unclipped tile_q x tile_k rectangle lies inside the buffer
+    and every pair is allowed.  PARTIAL: anything else.  Returns a uint8 matrix
+    [n_q_tiles, n_k_tiles].
+    """
+    T = D.shape[0]
+    nq = (T + tile_q - 1) // tile_q
+    nk = (T + tile_k - 1) // tile_k
+    cls = np.zeros((nq, nk), dtype=np.uint8)
+    for tq in range(nq):
+        q_lo, q_hi = tq * tile_q, min(T, (tq + 1) * tile_q)
+        # keys beyond the last query of the stripe fail the causal clause
+        k_end = q_hi
+        stripe = dense_mask(I_chosen, I_rejected, D, q_lo, q_hi, 0, k_end)
+        for tk in range((k_end + tile_k - 1) // tile_k):
+            k_lo, k_hi = tk * tile_k, min(T, (tk + 1) * tile_k)
+            blk = stripe[:, k_lo:min(k_hi, k_end)]
+            n_allowed = int(blk.sum())
+            if n_allowed == 0:
+                continue
+            unclipped = (q_hi - q_lo == tile_q) and (k_hi - k_lo == tile_k)
+            if unclipped and k_hi <= k_end and n_allowed == tile_q * tile_k:
+                cls[tq, tk] = FULL
+            else:
+                cls[tq, tk] = PARTIAL
+    return cls
+
+
+def csr_q_major(cls):
+    """q-major CSR of the non-skipped tiles: row_ptr[n_q+1], k-tile index
+    (ascending inside a row) and class of every entry."""
+    nq = cls.shape[0]
+    row_ptr = np.zeros(nq + 1, dtype=np.int32)
+    idx, cl = [], []
+    for tq in range(nq):
+        ks = np.nonzero(cls[tq])[0]
+        idx.append(ks.astype(np.int32))
+        cl.append(cls[tq, ks])
+        row_ptr[tq + 1] = row_ptr[tq] + len(ks)
+    idx = np.concatenate(idx) if idx else np.zeros(0, np.int32)
+    cl = np.concatenate(cl) if cl else np.zeros(0, np.uint8)
+    return row_ptr, idx.astype(np.int32), cl.astype(np.uint8)
+
+
+def csr_k_major(cls):
+    """k-major CSR (for dK/dV): row_ptr[n_k+1], q-tile index ascending, class."""
+    return csr_q_major(np.ascontiguousarray(cls.T))
+
+
+def token_descriptors(I_chosen, I_rejected, D):
+    """Per-token (s, hole_lo, hole_hi) as int32 [T, 3]: s = first token of the
+    token's document; (hole_lo, hole_hi) = (chosen start, rejected start) for
+    tokens of the rejected response (the keys they must not see), else (0, 0);
+    padding tokens get s = INT32_MAX."""
+    T = D.shape[0]
+    desc = np.zeros((T, 3), dtype=np.int32)
+    first = {}
+    for t in range(T):
+        d = int(D[t])
+        if d == PAD_DOC:
+            desc[t, 0] = PAD_START
+            continue
+        if d not in first:
+            first[d] = t
+        desc[t, 0] = first[d]
+        if I_rejected[t] <= t:
+            desc[t, 1] = I_chosen[t]
+            desc[t, 2] = I_rejected[t]
+    return desc
+
+
+# --------------------------------------------------------------------------
+# attention on one dense block
+# --------------------------------------------------------------------------
+def _softmax_block(q, k, allowed, scale):
+    """Scaled scores on allowed pairs, row softmax.  Returns P, LSE (fp64)."""
+    S = scale * (q @ k.T)
+    S = np.where(allowed, S, -np.inf)
+    m = S.max(axis=1) if S.shape[1] else np.full(S.shape[0], -np.inf)
+    m_fin = np.where(np.isfinite(m), m, 0.0)           # empty rows: avoid inf - inf
+    E = np.exp(S - m_fin[:, None])                     # exp(-inf) = 0 at masked pairs
+    l = E.sum(axis=1)
+    with np.errstate(divide="ignore", invalid="ignore"):
+        lse = m_fin + np.log(l)                        # -inf for an empty row
+        P = np.where(l[:, None] > 0, E / l[:, None], 0.0)
+    return P, lse
+
+
+def forward_block(q, k, v, allowed, scale):
+    """O = softmax(scale q k^T on allowed) v for one head, dense.  fp64."""
+    P, lse = _softmax_block(q, k, allowed, scale)
+    return P @ v, lse, P
+
+
+def backward_block(q, k, v, do, allowed, scale):
+    """Explicit softmax-attention backward for one head, dense.  fp64.
+    Returns dq, dk, dv, o, lse, delta."""
+    P, lse = _softmax_block(q, k, allowed, scale)
+    o = P @ v
+    delta = (do * o).sum(axis=1)
+    dv = P.T @ do
+    dP = do @ v.T
+    dS = P * (dP - delta[:, None])
+    dq = scale * (dS @ k)
+    dk = scale * (dS.T @ q)
+    return dq, dk, dv, o, lse, delta
+
+
+# --------------------------------------------------------------------------
+# whole-buffer drivers
+# --------------------------------------------------------------------------
+def _as64(x):
+    return np.asarray(x, dtype=np.float64)
+
+
+def _blocks(D, samples):
+    """Token ranges [lo, hi) of the documents to evaluate."""
+    ids = np.unique(D[D != PAD_DOC]) if samples is None else np.asarray(samples)
+    out = []
+    for i in ids:
+        t = np.nonzero(D == i)[0]
+        if len(t):
+            out.append((int(t[0]), int(t[-1]) + 1))
+    return out
+
+
+def forward(Q, K, V, scale, I_chosen, I_rejected, D, heads=None, samples=None, flat=False):
+    """Forward over the flat buffer.
+
+    Q [T, Hq, d], K, V [T, Hkv, d] (any float dtype; used as float64).
+    Returns O [T, Hq, d] and LSE [Hq, T].  Positions of padding tokens (and, when
+    `heads` / `samples` restrict the work, everything not requested) hold
+    O = 0 and LSE = -inf.  flat=True evaluates the whole T x T mask at once
+    instead of one dense block per document (tiny inputs only); the document
+    clause makes both forms identical.
+    """
+    T, Hq, d = Q.shape
+    Hkv = K.shape[1]
+    G = Hq // Hkv
+    O = np.zeros((T, Hq, d))
+    LSE = np.full((Hq, T), -np.inf)
+    ranges = [(0, T)] if flat else _blocks(D, samples)
+    for h in (range(Hq) if heads is None else heads):
+        g = h // G
+        for lo, hi in ranges:
+            allowed = dense_mask(I_chosen, I_rejected, D, lo, hi, lo, hi)
+            o, lse, _ = forward_block(_as64(Q[lo:hi, h]), _as64(K[lo:hi, g]), _as64(V[lo:hi, g]),
+                                      allowed, scale)
+            O[lo:hi, h] = o
+            LSE[h, lo:hi] = lse
+    return O, LSE
+
+
+def backward(Q, K, V, dO, scale, I_chosen, I_rejected, D, heads=None, samples=None, flat=False):
+    """Backward over the flat buffer from the oracle's own O and LSE.
+
+    Returns dict with dQ [T, Hq, d], dK, dV [T, Hkv, d], O, LSE [Hq, T],
+    delta [Hq, T].  dK and dV sum the contributions of the q-heads evaluated
+    (all G heads of a group unless `heads` restricts them): the prompt's keys
+    collect gradient from prompt, chosen and rejected queries alike.
+    """
+    T, Hq, d = Q.shape
+    Hkv = K.shape[1]
+    G = Hq // Hkv
+    out = dict(dQ=np.zeros((T, Hq, d)), dK=np.zeros((T, Hkv, d)), dV=np.zeros((T, Hkv, d)),
+               O=np.zeros((T, Hq, d)), LSE=np.full((Hq, T), -np.inf), delta=np.zeros((Hq, T)))
+    ranges = [(0, T)] if flat else _blocks(D, samples)
+    for h in (range(Hq) if heads is None else heads):
+        g = h // G
+        for lo, hi in ranges:
+            allowed = dense_mask(I_chosen, I_rejected, D, lo, hi, lo, hi)
+            dq, dk, dv, o, lse, delta = backward_block(
+                _as64(Q[lo:hi, h]), _as64(K[lo:hi, g]), _as64(V[lo:hi, g]), _as64(dO[lo:hi, h]),
+                allowed, scale)
+            out["dQ"][lo:hi, h] = dq
+            out["dK"][lo:hi, g] += dk
+            out["dV"][lo:hi, g] += dv
+            out["O"][lo:hi, h] = o
+            out["LSE"][h, lo:hi] = lse
+            out["delta"][h, lo:hi] = delta
+    return out
+
+
+def forward_rows(Q, K, V, scale, I_chosen, I_rejected, D, h, rows):
+    """O and LSE of individual query rows (one head), each computed from the
+    definition against all keys up to the row.  For spot checks at sizes where
+    the full problem is too large."""
+    Hq, Hkv = Q.shape[1], K.shape[1]
+    g = h // (Hq // Hkv)
+    O = np.zeros((len(rows), Q.shape[2]))
+    LSE = np.full(len(rows), -np.inf)
+    for n, i in enumerate(rows):
+        allowed = dense_mask(I_chosen, I_rejected, D, i, i + 1, 0, i + 1)
+        o, lse, _ = forward_block(_as64(Q[i:i + 1, h]), _as64(K[:i + 1, g]), _as64(V[:i + 1, g]),
+                                  allowed, scale)
+        O[n] = o[0]
+        LSE[n] = lse[0]
+    return O, LSE
