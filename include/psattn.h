@@ -1,0 +1,196 @@
+/*
+ * psattn — prefix-shared DPO attention for MI355X (gfx950), C ABI.
+ *
+ * One packed token buffer holds samples laid out as [prompt | chosen | rejected]
+ * (paper Section 3.1); several samples may share the buffer, with padding between
+ * or after them (Section 3.2, Section 4.3.2).  Attention is ordinary causal
+ * softmax attention restricted by the prefix-sharing mask of Algorithm 1, in its
+ * packed form of Algorithm 3:
+ *
+ *     allowed(q, kv) = kv <= q  &&  doc(q) == doc(kv)
+ *                      && !(R <= q && C <= kv < R)
+ *
+ * where C / R are the first chosen / rejected token of q's sample.  A sample with
+ * chosen_len = rejected_len = 0 is a plain causal document, which expresses the
+ * paper's baseline formats (Algorithm 2, the "normal paired format").
+ *
+ * The paper's (b, q) batch/position coordinates map to the flat token index
+ * b * L + q; rows are independent under the document clause, so a flat buffer with
+ * sample offsets covers both unpacked batches and packed, padded rows.
+ *
+ * Conventions
+ *   - every function returns PSATTN_OK (0) or a negative psattn_status; nothing
+ *     aborts or throws; psattn_strerror() names a code.
+ *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
+ *     memory of the current device.  The caller owns every tensor and the stream;
+ *     the library owns only the psattn_meta object (host arrays + one device
+ *     allocation), released by psattn_free_meta.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the null stream).  All
+ *     device work is enqueued on it and is asynchronous; no call synchronises
+ *     except where stated.
+ *   - tensors are contiguous, token-major: Q, O, dO, dQ are [T, n_q_heads, head_dim],
+ *     K, V, dK, dV are [T, n_kv_heads, head_dim], head_dim fastest.  LSE is
+ *     [n_q_heads, T] float.  q-heads [g*G, (g+1)*G), G = n_q_heads / n_kv_heads,
+ *     read kv-head g.
+ *   - padding tokens (covered by no sample) are never attended to; every output at
+ *     a padding position is written as zero (LSE = -inf).  Outputs are overwritten,
+ *     never accumulated into.
+ */
+#ifndef PSATTN_H
+#define PSATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct psattn_meta psattn_meta; /* opaque */
+
+typedef enum {
+    PSATTN_OK = 0,
+    PSATTN_EINVAL = -1,       /* null pointer, negative length, empty sample, bad heads / head_dim / tiles */
+    PSATTN_EOVERLAP = -2,     /* samples not sorted by offset, or overlapping */
+    PSATTN_ERANGE = -3,       /* a sample reaches beyond total_tokens */
+    PSATTN_ENOMEM = -4,       /* host or device allocation failed */
+    PSATTN_EHIP = -5,         /* a HIP runtime call failed */
+    PSATTN_EUNSUPPORTED = -6, /* valid request this build has no kernel for */
+    PSATTN_ENODEVICE = -7     /* meta was built host-only; no device copy to run kernels from */
+} psattn_status;
+
+typedef enum { PSATTN_F32 = 0, PSATTN_BF16 = 1 } psattn_dtype;
+
+/* tile classes of the block mask */
+enum { PSATTN_TILE_SKIPPED = 0, PSATTN_TILE_PARTIAL = 1, PSATTN_TILE_FULL = 2 };
+
+/* which tile grid of a meta object */
+enum { PSATTN_GRID_FWD = 0, /* q-major CSR, used by psattn_fwd and the dQ pass  */
+       PSATTN_GRID_BWD = 1  /* k-major CSR, used by the dK/dV pass              */ };
+
+/*
+ * Build the block mask for one mini-batch (Section 3.1: computed once per training
+ * step and reused by every attention layer and head).
+ *
+ * Samples: sample i covers flat tokens [offset[i], offset[i] + prefix_len[i] +
+ * chosen_len[i] + rejected_len[i]).  Samples must be sorted by offset and must not
+ * overlap; gaps and a tail are padding.  Each of the three lengths may be zero but
+ * not all three.  n_samples may be zero (everything is padding).
+ *
+ * Two tile grids over the flat buffer are classified, tile t = tokens
+ * [t*tile, min((t+1)*tile, T)):
+ *   FWD grid (tile_q x tile_k), stored q-major: for each q-tile the ascending list
+ *       of k-tiles that are not SKIPPED, with their class;
+ *   BWD grid (bwd_tile_q x bwd_tile_k), stored k-major: for each k-tile the
+ *       ascending list of q-tiles that are not SKIPPED.
+ * SKIPPED = no allowed pair; FULL = the unclipped rectangle lies inside the buffer
+ * and every pair is allowed (a kernel needs neither mask nor bounds check);
+ * PARTIAL = the rest.  A tile size of 0 selects the library default (the size the
+ * bf16 kernels are built for).  The cost is O(T + non-skipped tiles); the T x T mask
+ * is never materialised.
+ *
+ * Also derived: per-token descriptors (s, hole_lo, hole_hi): s = first token of the
+ * token's sample (INT32_MAX for padding); [hole_lo, hole_hi) = [C, R) for tokens of
+ * the rejected response, (0, 0) otherwise.  allowed(q, kv) == (s_q <= kv <= q &&
+ * !(hole_lo_q <= kv < hole_hi_q)).
+ *
+ * psattn_build_meta uploads the metadata to the current device with one
+ * asynchronous copy on hip_stream (the host staging buffer stays alive inside the
+ * object).  psattn_build_meta_host builds the same object without touching any
+ * device (for inspection and planning); kernels refuse it with PSATTN_ENODEVICE.
+ * On error *out is set to NULL.
+ */
+int psattn_build_meta(int32_t n_samples,
+                      const int32_t* offset,       /* host [n_samples] */
+                      const int32_t* prefix_len,   /* host [n_samples] */
+                      const int32_t* chosen_len,   /* host [n_samples] */
+                      const int32_t* rejected_len, /* host [n_samples] */
+                      int32_t total_tokens,        /* T, including padding */
+                      int32_t tile_q, int32_t tile_k,
+                      int32_t bwd_tile_q, int32_t bwd_tile_k,
+                      void* hip_stream,
+                      psattn_meta** out);
+
+int psattn_build_meta_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                           const int32_t* chosen_len, const int32_t* rejected_len,
+                           int32_t total_tokens, int32_t tile_q, int32_t tile_k,
+                           int32_t bwd_tile_q, int32_t bwd_tile_k, psattn_meta** out);
+
+/* Releases host and device memory of the object.  The caller must make sure no
+ * kernel that uses it is still running.  NULL is accepted. */
+int psattn_free_meta(psattn_meta* meta);
+
+/* Host read-back of the canonical metadata (pure host copies, no synchronisation).
+ * grid = PSATTN_GRID_FWD: rows are q-tiles, idx are k-tiles.
+ * grid = PSATTN_GRID_BWD: rows are k-tiles, idx are q-tiles. */
+int psattn_meta_tiles(const psattn_meta* meta, int32_t grid, int32_t* tile_q, int32_t* tile_k,
+                      int32_t* n_q_tiles, int32_t* n_k_tiles, int64_t* n_entries);
+int psattn_meta_copy_csr(const psattn_meta* meta, int32_t grid,
+                         int32_t* row_ptr, /* host [n_rows + 1]                      */
+                         int32_t* idx,     /* host [n_entries], ascending in a row   */
+                         uint8_t* cls);    /* host [n_entries], PARTIAL or FULL      */
+/* tok_desc: host [3 * T] = (s, hole_lo, hole_hi) per token. */
+int psattn_meta_copy_tok_desc(const psattn_meta* meta, int32_t* tok_desc);
+/* key_hi: host [T]; the queries allowed to read key j are exactly [j, key_hi[j])
+ * (the end of the chosen response for chosen keys, else the end of the sample;
+ * 0 for padding).  This is the mask seen from the key side, used by the dK/dV pass. */
+int psattn_meta_copy_key_desc(const psattn_meta* meta, int32_t* key_hi);
+/* Exact number of allowed (q, kv) pairs, from the closed form
+ * sum_i tri(p) + c*p + tri(c) + r*p + tri(r), tri(n) = n(n+1)/2. */
+int psattn_meta_allowed_pairs(const psattn_meta* meta, int64_t* n_allowed);
+
+/*
+ * Forward: O = softmax(scale * Q K^T restricted to allowed pairs) V and
+ * LSE[h, q] = log sum_kv exp(scale * Q_q . K_kv) (natural log).  SKIPPED tiles are
+ * never computed (Section 3.1).  dt selects the element type of Q, K, V, O
+ * (float, or bfloat16 with float accumulation); LSE is always float.
+ * head_dim: 64 or 128 for PSATTN_F32, 128 for PSATTN_BF16.
+ */
+int psattn_fwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
+               int32_t head_dim, float scale,
+               const void* Q, const void* K, const void* V, /* device */
+               void* O,                                     /* device [T, n_q_heads, head_dim] */
+               float* LSE,                                  /* device [n_q_heads, T]           */
+               void* hip_stream);
+
+/*
+ * Backward of psattn_fwd given dO, the forward's O and LSE: recomputes
+ * P = exp(S - LSE), then dV = P^T dO, dS = P o (dO V^T - delta), delta = rowsum(dO o O),
+ * dQ = scale dS K, dK = scale dS^T Q.  dK and dV of a kv-head sum over the G q-heads
+ * that read it; prompt keys collect gradient from prompt, chosen and rejected
+ * queries.  The paper times forward and backward together (Section 4.2).
+ *
+ * workspace: device scratch of at least psattn_bwd_workspace_bytes() bytes, owned by
+ * the caller, contents undefined on entry and exit (holds delta).
+ */
+int psattn_bwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
+               int32_t head_dim, float scale,
+               const void* Q, const void* K, const void* V, const void* O, const void* dO,
+               const float* LSE,                /* device, as written by psattn_fwd */
+               void* dQ, void* dK, void* dV,    /* device, fully overwritten        */
+               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+size_t psattn_bwd_workspace_bytes(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads,
+                                  int32_t head_dim);
+
+/*
+ * Per-pass device timing for benchmarks.  While enabled, psattn_fwd / psattn_bwd
+ * bracket each kernel with a pair of HIP events on the caller's stream (pass 0 =
+ * forward, 1 = delta, 2 = dQ, 3 = dK/dV).  psattn_profile_read waits for the
+ * recorded events, adds the elapsed milliseconds per pass to sum_ms[4] and the
+ * number of launches to count[4] (both host, overwritten), and forgets them.
+ * Not thread-safe; meant for one benchmarking thread.
+ */
+int psattn_profile_enable(int32_t on);
+int psattn_profile_read(double* sum_ms, int64_t* count);
+
+/* Name of the kernel launched last by psattn_fwd / psattn_bwd's passes, for
+ * profilers and benchmarks.  pass: 0 = forward, 1 = delta, 2 = dQ, 3 = dK/dV. */
+const char* psattn_kernel_name(int32_t dt, int32_t pass);
+
+const char* psattn_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSATTN_H */

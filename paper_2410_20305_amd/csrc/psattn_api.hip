@@ -1,0 +1,255 @@
+// C-ABI entry points that touch the device: metadata upload, argument checks and
+// kernel dispatch for psattn_fwd / psattn_bwd.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "psattn_internal.h"
+
+using namespace psattn;
+
+namespace {
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct BlobLayout {
+    size_t tok, f_row, f_ent, f_ord, b_row, b_ent, b_ord, total;
+};
+
+BlobLayout layout_of(const psattn_meta& m) {
+    BlobLayout L{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L.tok = take(sizeof(Tok4) * static_cast<size_t>(m.T));
+    L.f_row = take(sizeof(int32_t) * m.fwd.row_ptr.size());
+    L.f_ent = take(sizeof(int32_t) * m.fwd.idx.size());
+    L.f_ord = take(sizeof(int32_t) * m.fwd.order.size());
+    L.b_row = take(sizeof(int32_t) * m.bwd.row_ptr.size());
+    L.b_ent = take(sizeof(int32_t) * m.bwd.idx.size());
+    L.b_ord = take(sizeof(int32_t) * m.bwd.order.size());
+    L.total = off ? off : 256;
+    return L;
+}
+
+void fill_csr(char* base, size_t row, size_t ent, size_t ord, const TileCsr& g) {
+    std::memcpy(base + row, g.row_ptr.data(), g.row_ptr.size() * sizeof(int32_t));
+    int32_t* e = reinterpret_cast<int32_t*>(base + ent);
+    for (size_t i = 0; i < g.idx.size(); ++i) e[i] = (g.idx[i] << 2) | g.cls[i];
+    std::memcpy(base + ord, g.order.data(), g.order.size() * sizeof(int32_t));
+}
+
+DeviceCsr view_csr(const char* base, size_t row, size_t ent, size_t ord, const TileCsr& g) {
+    DeviceCsr v{};
+    v.row_ptr = reinterpret_cast<const int32_t*>(base + row);
+    v.entry = reinterpret_cast<const int32_t*>(base + ent);
+    v.order = reinterpret_cast<const int32_t*>(base + ord);
+    v.n_rows = static_cast<int32_t>(g.row_ptr.size()) - 1;
+    v.tile_q = g.tile_q;
+    v.tile_k = g.tile_k;
+    return v;
+}
+
+int upload(psattn_meta* m, hipStream_t stream) {
+    const BlobLayout L = layout_of(*m);
+    if (hipGetDevice(&m->device) != hipSuccess) return PSATTN_EHIP;
+    if (hipHostMalloc(&m->h_stage, L.total, hipHostMallocDefault) != hipSuccess) {
+        m->h_stage = nullptr;
+        (void)hipGetLastError();
+        return PSATTN_ENOMEM;
+    }
+    if (hipMalloc(&m->d_blob, L.total) != hipSuccess) {
+        m->d_blob = nullptr;
+        (void)hipGetLastError();
+        return PSATTN_ENOMEM;
+    }
+    char* h = static_cast<char*>(m->h_stage);
+    std::memset(h, 0, L.total);
+    Tok4* tok = reinterpret_cast<Tok4*>(h + L.tok);
+    for (int32_t t = 0; t < m->T; ++t)
+        tok[t] = Tok4{m->tok_desc[3 * t], m->tok_desc[3 * t + 1], m->tok_desc[3 * t + 2], m->key_hi[t]};
+    fill_csr(h, L.f_row, L.f_ent, L.f_ord, m->fwd);
+    fill_csr(h, L.b_row, L.b_ent, L.b_ord, m->bwd);
+    if (hipMemcpyAsync(m->d_blob, h, L.total, hipMemcpyHostToDevice, stream) != hipSuccess) {
+        (void)hipGetLastError();
+        return PSATTN_EHIP;
+    }
+    const char* d = static_cast<const char*>(m->d_blob);
+    m->blob_bytes = L.total;
+    m->dev.tok = reinterpret_cast<const Tok4*>(d + L.tok);
+    m->dev.fwd = view_csr(d, L.f_row, L.f_ent, L.f_ord, m->fwd);
+    m->dev.bwd = view_csr(d, L.b_row, L.b_ent, L.b_ord, m->bwd);
+    m->dev.T = m->T;
+    m->on_device = true;
+    return PSATTN_OK;
+}
+
+int check_common(const psattn_meta* meta, int32_t dt, int32_t Hq, int32_t Hkv, int32_t d) {
+    if (!meta) return PSATTN_EINVAL;
+    if (dt != PSATTN_F32 && dt != PSATTN_BF16) return PSATTN_EINVAL;
+    if (Hq <= 0 || Hkv <= 0 || Hq % Hkv != 0) return PSATTN_EINVAL;
+    if (d != 64 && d != 128) return PSATTN_EINVAL;
+    if (!meta->on_device) return PSATTN_ENODEVICE;
+    // tile * heads products must fit the 1-D grid
+    if (static_cast<int64_t>(meta->fwd.n_q_tiles) * Hq > INT32_MAX) return PSATTN_EUNSUPPORTED;
+    return PSATTN_OK;
+}
+
+// The MFMA kernels fold the scale into a base-2 exponent and take row maxima before
+// scaling, which needs scale > 0; anything else runs on the generic kernels.
+bool mfma_fwd_ok(const psattn_meta* m, int32_t dt, int32_t d, float scale) {
+    return dt == PSATTN_BF16 && d == 128 && scale > 0.f && m->fwd.tile_q == kFwdTileQ &&
+           m->fwd.tile_k == kFwdTileK;
+}
+bool mfma_bwd_ok(const psattn_meta* m, int32_t dt, int32_t d, float scale) {
+    return mfma_fwd_ok(m, dt, d, scale) && m->bwd.tile_q == kBwdTileQ && m->bwd.tile_k == kBwdTileK;
+}
+
+// ---- optional per-pass event timing
+bool g_profile = false;
+struct EventPair { hipEvent_t a, b; int pass; };
+std::vector<EventPair> g_events;
+
+struct PassTimer {
+    hipStream_t stream;
+    EventPair ev{};
+    bool active = false;
+    PassTimer(int pass, void* s) : stream(static_cast<hipStream_t>(s)) {
+        if (!g_profile) return;
+        if (hipEventCreate(&ev.a) != hipSuccess) return;
+        if (hipEventCreate(&ev.b) != hipSuccess) { (void)hipEventDestroy(ev.a); return; }
+        ev.pass = pass;
+        active = hipEventRecord(ev.a, stream) == hipSuccess;
+    }
+    ~PassTimer() {
+        if (!active) return;
+        (void)hipEventRecord(ev.b, stream);
+        g_events.push_back(ev);
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+int psattn_profile_enable(int32_t on) {
+    g_profile = on != 0;
+    return PSATTN_OK;
+}
+
+int psattn_profile_read(double* sum_ms, int64_t* count) {
+    if (!sum_ms || !count) return PSATTN_EINVAL;
+    for (int i = 0; i < 4; ++i) { sum_ms[i] = 0.0; count[i] = 0; }
+    int rc = PSATTN_OK;
+    for (EventPair& e : g_events) {
+        float ms = 0.f;
+        if (hipEventSynchronize(e.b) != hipSuccess || hipEventElapsedTime(&ms, e.a, e.b) != hipSuccess) rc = PSATTN_EHIP;
+        else { sum_ms[e.pass] += ms; count[e.pass]++; }
+        (void)hipEventDestroy(e.a);
+        (void)hipEventDestroy(e.b);
+    }
+    g_events.clear();
+    return rc;
+}
+
+int psattn_build_meta(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                      const int32_t* chosen_len, const int32_t* rejected_len, int32_t total_tokens,
+                      int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
+                      void* hip_stream, psattn_meta** out) {
+    psattn_meta* m = nullptr;
+    int rc = build_host(n_samples, offset, prefix_len, chosen_len, rejected_len, total_tokens, tile_q,
+                        tile_k, bwd_tile_q, bwd_tile_k, &m);
+    if (rc != PSATTN_OK) return rc;
+    rc = upload(m, static_cast<hipStream_t>(hip_stream));
+    if (rc != PSATTN_OK) {
+        psattn_free_meta(m);
+        *out = nullptr;
+        return rc;
+    }
+    *out = m;
+    return PSATTN_OK;
+}
+
+int psattn_free_meta(psattn_meta* meta) {
+    if (!meta) return PSATTN_OK;
+    int rc = PSATTN_OK;
+    if (meta->d_blob && hipFree(meta->d_blob) != hipSuccess) rc = PSATTN_EHIP;
+    if (meta->h_stage && hipHostFree(meta->h_stage) != hipSuccess) rc = PSATTN_EHIP;
+    delete meta;
+    return rc;
+}
+
+int psattn_fwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
+               int32_t head_dim, float scale, const void* Q, const void* K, const void* V, void* O,
+               float* LSE, void* hip_stream) {
+    int rc = check_common(meta, dt, n_q_heads, n_kv_heads, head_dim);
+    if (rc != PSATTN_OK) return rc;
+    if (meta->T == 0) return PSATTN_OK;
+    if (!Q || !K || !V || !O || !LSE) return PSATTN_EINVAL;
+    AttnArgs a{};
+    a.meta = meta->dev;
+    a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = scale;
+    a.Q = Q; a.K = K; a.V = V; a.Oout = O; a.LSEout = LSE;
+    int err;
+    {
+        PassTimer t(0, hip_stream);
+        err = mfma_fwd_ok(meta, dt, head_dim, scale) ? launch_mfma_fwd(a, hip_stream)
+                                                     : launch_generic_fwd(dt, a, hip_stream);
+    }
+    return err == 0 ? PSATTN_OK : PSATTN_EHIP;
+}
+
+size_t psattn_bwd_workspace_bytes(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads,
+                                  int32_t head_dim) {
+    (void)n_kv_heads; (void)head_dim;
+    if (!meta || n_q_heads <= 0) return 0;
+    return align_up(sizeof(float) * static_cast<size_t>(meta->T) * n_q_heads, 256) + 256;
+}
+
+int psattn_bwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
+               int32_t head_dim, float scale, const void* Q, const void* K, const void* V,
+               const void* O, const void* dO, const float* LSE, void* dQ, void* dK, void* dV,
+               void* workspace, size_t workspace_bytes, void* hip_stream) {
+    int rc = check_common(meta, dt, n_q_heads, n_kv_heads, head_dim);
+    if (rc != PSATTN_OK) return rc;
+    if (meta->T == 0) return PSATTN_OK;
+    if (!Q || !K || !V || !O || !dO || !LSE || !dQ || !dK || !dV || !workspace) return PSATTN_EINVAL;
+    if (workspace_bytes < psattn_bwd_workspace_bytes(meta, n_q_heads, n_kv_heads, head_dim)) return PSATTN_EINVAL;
+    AttnArgs a{};
+    a.meta = meta->dev;
+    a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = scale;
+    a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.LSE = LSE;
+    a.dQ = dQ; a.dK = dK; a.dV = dV;
+    a.delta = reinterpret_cast<float*>(align_up(reinterpret_cast<uintptr_t>(workspace), 256));
+    int err;
+    {
+        PassTimer t(1, hip_stream);
+        err = launch_delta(dt, a, hip_stream);
+    }
+    if (err) return PSATTN_EHIP;
+    const bool mfma = mfma_bwd_ok(meta, dt, head_dim, scale);
+    {
+        PassTimer t(2, hip_stream);
+        err = mfma ? launch_mfma_dq(a, hip_stream) : launch_generic_dq(dt, a, hip_stream);
+    }
+    if (err) return PSATTN_EHIP;
+    {
+        PassTimer t(3, hip_stream);
+        err = mfma ? launch_mfma_dkdv(a, hip_stream) : launch_generic_dkdv(dt, a, hip_stream);
+    }
+    return err == 0 ? PSATTN_OK : PSATTN_EHIP;
+}
+
+const char* psattn_kernel_name(int32_t dt, int32_t pass) {
+    const bool bf = dt == PSATTN_BF16;
+    switch (pass) {
+        case 0: return bf ? "psattn_fwd_bf16_mfma" : "generic_fwd";
+        case 1: return "delta_kernel";
+        case 2: return bf ? "psattn_dq_bf16_mfma" : "generic_dq";
+        case 3: return bf ? "psattn_dkdv_bf16_mfma" : "generic_dkdv";
+        default: return "";
+    }
+}
+
+}  // extern "C"

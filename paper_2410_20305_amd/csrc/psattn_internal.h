@@ -1,0 +1,96 @@
+// Internal declarations shared by the host metadata builder, the C-ABI entry
+// points and the kernel launchers of libpsattn.  Not part of the public ABI.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <vector>
+
+#include "psattn.h"
+
+namespace psattn {
+
+constexpr int32_t kPadStart = INT32_MAX;
+
+// Default tile grids = the shapes the bf16 MFMA kernels are built for.
+constexpr int32_t kFwdTileQ = 128;
+constexpr int32_t kFwdTileK = 64;
+constexpr int32_t kBwdTileQ = 64;
+constexpr int32_t kBwdTileK = 128;
+
+// One CSR over a tile grid.  entry = (column tile index << 2) | class.
+struct TileCsr {
+    int32_t tile_q = 0, tile_k = 0;
+    int32_t n_q_tiles = 0, n_k_tiles = 0;
+    std::vector<int32_t> row_ptr;  // rows = q-tiles (FWD) or k-tiles (BWD)
+    std::vector<int32_t> idx;
+    std::vector<uint8_t> cls;
+    std::vector<int32_t> order;    // rows sorted by decreasing work (longest first)
+};
+
+// Device-side view handed to kernels by value.
+struct DeviceCsr {
+    const int32_t* row_ptr;
+    const int32_t* entry;  // (idx << 2) | cls
+    const int32_t* order;
+    int32_t n_rows;
+    int32_t tile_q, tile_k;
+};
+
+// Per-token descriptor as the kernels read it (one 16-byte load).
+struct alignas(16) Tok4 {
+    int32_t s, hole_lo, hole_hi, key_hi;
+};
+
+struct DeviceMeta {
+    const Tok4* tok;        // [T]
+    DeviceCsr fwd, bwd;
+    int32_t T;
+};
+
+}  // namespace psattn
+
+struct psattn_meta {
+    int32_t T = 0;
+    int32_t n_samples = 0;
+    int64_t n_allowed = 0;
+    std::vector<int32_t> tok_desc;  // [3T]  (s, hole_lo, hole_hi)
+    std::vector<int32_t> key_hi;    // [T]   queries that may read key j are [j, key_hi[j])
+    psattn::TileCsr fwd, bwd;
+    // device copy
+    bool on_device = false;
+    int device = -1;
+    void* d_blob = nullptr;
+    void* h_stage = nullptr;  // pinned staging buffer, alive until free
+    size_t blob_bytes = 0;
+    psattn::DeviceMeta dev{};
+};
+
+namespace psattn {
+
+// Host-only construction (psattn_meta.cpp).  Returns a psattn_status.
+int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+               const int32_t* chosen_len, const int32_t* rejected_len, int32_t total_tokens,
+               int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
+               psattn_meta** out);
+
+struct AttnArgs {
+    DeviceMeta meta;
+    int32_t Hq, Hkv, d;
+    float scale;
+    const void *Q, *K, *V, *O, *dO;
+    const float* LSE;
+    void *Oout, *dQ, *dK, *dV;
+    float* LSEout;
+    float* delta;  // [Hq, T]
+};
+
+// Launchers (each returns a hipError_t cast to int; 0 = success).
+int launch_generic_fwd(int dt, const AttnArgs& a, void* stream);
+int launch_generic_dq(int dt, const AttnArgs& a, void* stream);
+int launch_generic_dkdv(int dt, const AttnArgs& a, void* stream);
+int launch_delta(int dt, const AttnArgs& a, void* stream);
+int launch_mfma_fwd(const AttnArgs& a, void* stream);
+int launch_mfma_dq(const AttnArgs& a, void* stream);
+int launch_mfma_dkdv(const AttnArgs& a, void* stream);
+
+}  // namespace psattn

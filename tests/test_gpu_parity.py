@@ -1,0 +1,176 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same
+seeded inputs.  Tolerances: fp32 max-abs <= 1e-5 on every output; bf16 O max-abs
+<= 1e-2, LSE max-abs <= 1e-3, dQ/dK/dV relative L2 <= 2e-2 per tensor."""
+import numpy as np
+import pytest
+
+import paper_2410_20305_amd as ps
+import psattn_workloads as W
+from oracle import psattn_oracle as orc
+from gpu_util import check_padding_zero, oracle_arrays, rel_l2, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+F32_TOL = 1e-5
+BF16_O_TOL, BF16_LSE_TOL, BF16_GRAD_TOL = 1e-2, 1e-3, 2e-2
+
+
+def compare_full(w, tens, out, tol_kind):
+    Ic, Ir, D = oracle_arrays(w)
+    ref = orc.backward(tens["Q"], tens["K"], tens["V"], tens["dO"], w.scale, Ic, Ir, D)
+    real = D != orc.PAD_DOC
+    check_padding_zero(out, D)
+    for name in ("O", "dQ", "dK", "dV"):
+        assert np.all(np.isfinite(out[name])), name
+    if tol_kind == "f32":
+        for name in ("O", "dQ", "dK", "dV"):
+            err = np.abs(out[name] - ref[name]).max() if out[name].size else 0.0
+            assert err <= F32_TOL, (name, err)
+        err = np.abs(out["LSE"][:, real] - ref["LSE"][:, real]).max() if real.any() else 0.0
+        assert err <= F32_TOL, ("LSE", err)
+    else:
+        err = np.abs(out["O"] - ref["O"]).max() if out["O"].size else 0.0
+        assert err <= BF16_O_TOL, ("O", err)
+        err = np.abs(out["LSE"][:, real] - ref["LSE"][:, real]).max() if real.any() else 0.0
+        assert err <= BF16_LSE_TOL, ("LSE", err)
+        for name in ("dQ", "dK", "dV"):
+            e = rel_l2(out[name], ref[name])
+            assert e <= BF16_GRAD_TOL, (name, e)
+    return ref
+
+
+def test_config1_fp32():
+    w = W.make_workload("cfg1")
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    compare_full(w, tens, out, "f32")
+
+
+@pytest.mark.parametrize("tiles", [(16, 8, 8, 32), (5, 3, 7, 2), (128, 64, 64, 128), (64, 64, 64, 64)])
+@pytest.mark.parametrize("d,hq,hkv", [(64, 2, 1), (128, 4, 2)])
+def test_fp32_generic_shapes(tiles, d, hq, hkv):
+    """fp32 kernels on arbitrary tile grids, GQA, two samples with padding and a ragged tail."""
+    w = W.custom_workload([(23, 9, 14), (5, 0, 11), (0, 7, 3)], offsets=[3, 52, 70], total_tokens=83,
+                          hq=hq, hkv=hkv, d=d, dtype="f32", seed=11)
+    tens = W.make_tensors(w)
+    out, meta = run_gpu(w, tens, tiles)
+    compare_full(w, tens, out, "f32")
+
+
+BF16_CASES = {
+    # several 128-query tiles and 64-key tiles, ragged tails, padding inside and after
+    "two_samples_padding": dict(samples=[(150, 40, 70), (30, 90, 10)], offsets=[5, 300], T=450, hq=4, hkv=2),
+    "one_long": dict(samples=[(300, 129, 65)], offsets=[0], T=494, hq=2, hkv=1),
+    "no_prefix_no_chosen": dict(samples=[(0, 70, 90), (64, 0, 64), (1, 1, 1)], offsets=[0, 160, 288], T=291, hq=2, hkv=2),
+    "tiny": dict(samples=[(1, 0, 0)], offsets=[0], T=1, hq=1, hkv=1),
+    "all_padding": dict(samples=[], offsets=[], T=130, hq=2, hkv=1),
+    "exact_tiles": dict(samples=[(128, 64, 64)], offsets=[0], T=256, hq=8, hkv=2),
+}
+
+
+@pytest.mark.parametrize("case", sorted(BF16_CASES))
+def test_bf16_mfma_small(case):
+    c = BF16_CASES[case]
+    w = W.custom_workload(c["samples"], offsets=c["offsets"], total_tokens=c["T"], hq=c["hq"], hkv=c["hkv"],
+                          d=128, dtype="bf16", seed=21)
+    tens = W.make_tensors(w)
+    out, meta = run_gpu(w, tens)
+    assert meta.tiles(ps.GRID_FWD)["tile_q"] == 128  # default grid = the MFMA kernels
+    compare_full(w, tens, out, "bf16")
+
+
+@pytest.mark.parametrize("tiles,d", [((32, 16, 16, 32), 128), ((0, 0, 0, 0), 64), ((7, 5, 3, 9), 64)])
+def test_bf16_generic_kernels(tiles, d):
+    w = W.custom_workload([(40, 17, 25), (9, 30, 0)], offsets=[2, 90], total_tokens=131, hq=4, hkv=2,
+                          d=d, dtype="bf16", seed=31)
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens, tiles)
+    compare_full(w, tens, out, "bf16")
+
+
+def test_bf16_padding_values_do_not_leak():
+    w = W.custom_workload([(100, 30, 50), (20, 60, 10)], offsets=[7, 200], total_tokens=300, hq=2, hkv=1,
+                          d=128, dtype="bf16", seed=41)
+    tens = W.make_tensors(w)
+    out1, _ = run_gpu(w, tens)
+    _, _, D = oracle_arrays(w)
+    pad = D == orc.PAD_DOC
+    tens2 = {k: v.copy() for k, v in tens.items()}
+    for k in tens2:
+        tens2[k][pad] = 3.0e4
+    out2, _ = run_gpu(w, tens2)
+    for name in ("O", "LSE", "dQ", "dK", "dV"):
+        assert np.array_equal(out1[name], out2[name]), name
+
+
+def test_bf16_deterministic():
+    w = W.custom_workload([(200, 50, 80)], hq=4, hkv=1, d=128, dtype="bf16", seed=51)
+    tens = W.make_tensors(w)
+    a, _ = run_gpu(w, tens)
+    b, _ = run_gpu(w, tens)
+    for name in a:
+        assert np.array_equal(a[name], b[name]), name
+
+
+def test_config2_full():
+    """Second configuration, every head and sample, against the full oracle."""
+    w = W.make_workload("cfg2")
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    compare_full(w, tens, out, "bf16")
+
+
+def compare_subset(w, tens, out, samples, kv_heads, n_rows=64, seed=0):
+    """Full-size configurations: dense oracle on chosen (sample, kv-group) blocks —
+    which makes dK/dV of those blocks complete — plus single query rows elsewhere."""
+    Ic, Ir, D = oracle_arrays(w)
+    G = w.n_q_heads // w.n_kv_heads
+    check_padding_zero(out, D)
+    for name in ("O", "dQ", "dK", "dV"):
+        assert np.all(np.isfinite(out[name])), name
+    for g in kv_heads:
+        heads = list(range(g * G, (g + 1) * G))
+        ref = orc.backward(tens["Q"], tens["K"], tens["V"], tens["dO"], w.scale, Ic, Ir, D, heads=heads,
+                           samples=samples)
+        for s in samples:
+            o = int(w.offset[s])
+            n = int(w.prefix_len[s] + w.chosen_len[s] + w.rejected_len[s])
+            sl = slice(o, o + n)
+            err = np.abs(out["O"][sl][:, heads] - ref["O"][sl][:, heads]).max()
+            assert err <= BF16_O_TOL, ("O", s, g, err)
+            err = np.abs(out["LSE"][heads][:, sl] - ref["LSE"][heads][:, sl]).max()
+            assert err <= BF16_LSE_TOL, ("LSE", s, g, err)
+            e = rel_l2(out["dQ"][sl][:, heads], ref["dQ"][sl][:, heads])
+            assert e <= BF16_GRAD_TOL, ("dQ", s, g, e)
+            for name in ("dK", "dV"):
+                e = rel_l2(out[name][sl][:, g], ref[name][sl][:, g])
+                assert e <= BF16_GRAD_TOL, (name, s, g, e)
+    rng = np.random.default_rng(seed)
+    real = np.nonzero(D != orc.PAD_DOC)[0]
+    for h in rng.choice(w.n_q_heads, size=4, replace=False):
+        rows = rng.choice(real, size=n_rows // 4, replace=False)
+        Or, Lr = orc.forward_rows(tens["Q"], tens["K"], tens["V"], w.scale, Ic, Ir, D, int(h), rows.tolist())
+        assert np.abs(out["O"][rows, h] - Or).max() <= BF16_O_TOL
+        assert np.abs(out["LSE"][h, rows] - Lr).max() <= BF16_LSE_TOL
+
+
+def test_config3_sampled():
+    w = W.make_workload("cfg3")
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    compare_subset(w, tens, out, samples=[0, 9], kv_heads=[5])
+
+
+def test_config4_sampled():
+    w = W.make_workload("cfg4")
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    # first / last sample of a row, neighbours across a row boundary, the last sample
+    compare_subset(w, tens, out, samples=[0, 1, 17, 18, 19, 70, 141, 142], kv_heads=[0, 7])
+
+
+def test_config5_sampled():
+    w = W.make_workload("cfg5")
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    compare_subset(w, tens, out, samples=[4], kv_heads=[3], n_rows=32)
