@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the prefix-shared DPO attention hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--no-extras]
+
+One step = one pass of the whole hot path over one synthetic batch: block-mask
+build (psattn_build_meta), forward (psattn_fwd) and backward (psattn_bwd: delta,
+dQ, dK/dV).  Inputs are resident in HBM before the timed region.  Prints ONE JSON
+line.  `value` is useful attention TFLOP/s (14 * d * Hq * N_allowed FLOPs per
+step; masked pairs, padding and recomputation earn nothing).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+PEAK_HBM_GBS = 8000.0
+
+
+def tri(n):
+    return n * (n + 1) // 2
+
+
+def allowed_pairs(w):
+    p, c, r = (x.astype(np.int64) for x in (w.prefix_len, w.chosen_len, w.rejected_len))
+    return int((tri(p) + c * p + tri(c) + r * p + tri(r)).sum())
+
+
+def algorithmic_bytes(w, tokens):
+    """Bytes the method itself must move, each tensor once (bf16: e = 2)."""
+    e = 4 if w.dtype == "f32" else 2
+    Hq, Hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
+    fwd = (Hq + 2 * Hkv) * d * e + Hq * d * e + 4 * Hq
+    bwd = (3 * Hq + 2 * Hkv) * d * e + 8 * Hq + (Hq + 2 * Hkv) * d * e
+    return tokens * (fwd + bwd)
+
+
+class Runner:
+    """Device tensors of one workload + the three library calls of a step."""
+
+    def __init__(self, w, tensors=None, seed=0):
+        import torch
+        import paper_2410_20305_amd as ps
+        self.ps, self.torch, self.w = ps, torch, w
+        dt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+        T, Hq, Hkv, d = w.total_tokens, w.n_q_heads, w.n_kv_heads, w.head_dim
+        if tensors is not None:
+            mk = lambda n: torch.from_numpy(tensors[n]).to("cuda").to(dt)
+            self.Q, self.K, self.V, self.dO = mk("Q"), mk("K"), mk("V"), mk("dO")
+        else:  # same distribution, drawn on the device
+            g = torch.Generator(device="cuda")
+            g.manual_seed(1000 + seed)
+            mk = lambda h: torch.randn((T, h, d), generator=g, device="cuda", dtype=torch.float32).to(dt)
+            self.Q, self.K, self.V, self.dO = mk(Hq), mk(Hkv), mk(Hkv), mk(Hq)
+        self.O = torch.empty_like(self.Q)
+        self.LSE = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
+        self.dQ, self.dK, self.dV = torch.empty_like(self.Q), torch.empty_like(self.K), torch.empty_like(self.V)
+        meta = self.build_meta()
+        self.ws = torch.empty(ps.psattn_bwd_workspace_bytes(meta, Hq, Hkv, d), dtype=torch.uint8, device="cuda")
+        meta.free()
+        self.flops = 14 * d * Hq * allowed_pairs(w)
+
+    def build_meta(self):
+        w = self.w
+        return self.ps.psattn_build_meta(w.offset, w.prefix_len, w.chosen_len, w.rejected_len, w.total_tokens)
+
+    def step(self):
+        ps, w = self.ps, self.w
+        meta = self.build_meta()
+        ps.psattn_fwd(meta, self.Q, self.K, self.V, w.scale, O=self.O, LSE=self.LSE)
+        ps.psattn_bwd(meta, self.Q, self.K, self.V, self.O, self.dO, self.LSE, w.scale, dQ=self.dQ,
+                      dK=self.dK, dV=self.dV, workspace=self.ws)
+        return meta
+
+    def timed(self, steps, warmup):
+        """Wall time of `steps` whole steps, bracketed by synchronize; plus per-pass
+        kernel time from HIP events recorded by the library on the launch stream."""
+        torch, ps = self.torch, self.ps
+        keep = []
+        for _ in range(warmup):
+            keep.append(self.step())
+        torch.cuda.synchronize()
+        for m in keep:
+            m.free()
+        keep = []
+        ps.psattn_profile_enable(True)
+        ps.psattn_profile_read()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            keep.append(self.step())
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        ms, cnt = ps.psattn_profile_read()
+        ps.psattn_profile_enable(False)
+        for m in keep:
+            m.free()
+        per_pass = [float(ms[i] / max(1, cnt[i])) for i in range(4)]
+        return (t1 - t0) / steps * 1e3, per_pass
+
+
+def summarize(w, ms_step, per_pass, flops):
+    kern = sum(per_pass)
+    return dict(ms_per_step=round(ms_step, 4), ms_kernels=round(kern, 4),
+                ms_fwd=round(per_pass[0], 4), ms_delta=round(per_pass[1], 4), ms_dq=round(per_pass[2], 4),
+                ms_dkdv=round(per_pass[3], 4),
+                useful_tflops=round(flops / (ms_step * 1e-3) / 1e12, 2),
+                useful_tflops_kernels_only=round(flops / (kern * 1e-3) / 1e12, 2) if kern > 0 else None,
+                pct_mfma_peak=round(100 * flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2))
+
+
+def cpu_baseline(w, tens, budget_s=20.0):
+    """The oracle as it stands, timed on this host on a bounded sample of the
+    workload: whole (sample, kv-group) blocks, forward + backward, until the budget
+    is used.  Reported in the metric's unit (useful TFLOP/s of the blocks done)."""
+    from oracle import psattn_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    Ic, Ir, D = orc.index_arrays(w.offset, w.prefix_len, w.chosen_len, w.rejected_len, w.total_tokens)
+    G = w.n_q_heads // w.n_kv_heads
+    done_flops, done_token_heads, blocks = 0, 0, 0
+    t0 = time.perf_counter()
+    for g in range(w.n_kv_heads):
+        for s in range(w.n_samples):
+            heads = list(range(g * G, (g + 1) * G))
+            orc.backward(tens["Q"], tens["K"], tens["V"], tens["dO"], w.scale, Ic, Ir, D, heads=heads, samples=[s])
+            p, c, r = int(w.prefix_len[s]), int(w.chosen_len[s]), int(w.rejected_len[s])
+            n_allowed = tri(p) + c * p + tri(c) + r * p + tri(r)
+            done_flops += 14 * w.head_dim * G * n_allowed
+            done_token_heads += (p + c + r) * G
+            blocks += 1
+            if time.perf_counter() - t0 > budget_s:
+                break
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    return dict(value=round(done_flops / dt / 1e12, 6), unit="TFLOP/s", cores=int(cores), kind="oracle",
+                sample="%d of %d (sample, kv-group) blocks, each with its %d q-heads, fwd+bwd, fp64 numpy, "
+                       "%.1f s; tokens_per_s scales the blocks done to all %d q-heads" %
+                       (blocks, w.n_samples * w.n_kv_heads, G, dt, w.n_q_heads),
+                tokens_per_s=round(done_token_heads / w.n_q_heads / dt, 1))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--no-extras", action="store_true", help="skip the other configurations and the paired baseline")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path "
+              "(samples and kv-head groups are independent, so N GPUs would each run this same kernel "
+              "on their share with no exchange step).  Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2410_20305_amd as ps
+    import psattn_workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU: the HIP library has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    ps.load_library()
+    torch.cuda.set_device(0)
+
+    w = W.make_workload(args.workload)
+    tens = W.make_tensors(w)
+    run = Runner(w, tens)
+    ms_step, per_pass = run.timed(args.steps, args.warmup)
+    main_res = summarize(w, ms_step, per_pass, run.flops)
+    value = run.flops / (ms_step * 1e-3) / 1e12
+
+    # dominant kernel and its roofline: bf16 MFMA contraction
+    names = ["fwd", "delta", "dq", "dkdv"]
+    # algorithmic FLOPs per launch: forward 4, dK/dV pass 8 (S, dP, dV, dK), dQ pass 2 (dQ only;
+    # its recomputation of S and dP is overhead), in units of d * Hq * N_allowed
+    alg = [4, 0, 2, 8]
+    dom = max((0, 2, 3), key=lambda i: per_pass[i])
+    n_allowed = allowed_pairs(w)
+    ach = alg[dom] * w.head_dim * w.n_q_heads * n_allowed / (per_pass[dom] * 1e-3) / 1e12
+    roofline = dict(bound="mfma", kernel=ps.psattn_kernel_name(1, dom), achieved=round(ach, 2),
+                    peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    avg_launch_ms=round(per_pass[dom], 4),
+                    algorithmic_flops_per_launch=alg[dom] * w.head_dim * w.n_q_heads * n_allowed)
+
+    out = {
+        "metric": "useful attn TFLOP/s fwd+bwd", "value": round(value, 3), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "n_samples": w.n_samples, "tokens": w.unique_tokens,
+                   "buffer_tokens": w.total_tokens, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
+                   "head_dim": w.head_dim, "allowed_pairs": n_allowed,
+                   "step": "build_meta + fwd + bwd(delta, dQ, dK/dV)"},
+        "pct_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
+        "tokens_per_s": round(w.unique_tokens / (ms_step * 1e-3), 1),
+        "detail": main_res,
+        "roofline": roofline,
+    }
+    algb = algorithmic_bytes(w, w.total_tokens)
+    out["hbm_algorithmic_GBs"] = round(algb / (sum(per_pass) * 1e-3) / 1e9, 1)
+
+    if not args.no_extras:
+        extras = {}
+        for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+            wx = W.make_workload(name)
+            steps = max(5, min(args.steps, 20))
+            rx = run if name == args.workload else Runner(wx, None, seed=wx.seed)
+            ms_s, pp = (ms_step, per_pass) if name == args.workload else rx.timed(steps, 3)
+            res = summarize(wx, ms_s, pp, rx.flops)
+            res["tokens_per_s"] = round(wx.unique_tokens / (ms_s * 1e-3), 1)
+            # unshared paired baseline on the same samples, same kernels
+            pw, _, _ = W.paired_workload(wx)
+            rp = Runner(pw, None, seed=wx.seed)
+            ms_p, pp_p = rp.timed(steps, 3)
+            res["paired_ms_per_step"] = round(ms_p, 4)
+            res["paired_tokens_per_s"] = round(wx.unique_tokens / (ms_p * 1e-3), 1)
+            res["speedup_vs_paired"] = round(ms_p / ms_s, 3)
+            res["speedup_vs_paired_kernels_only"] = round(sum(pp_p) / sum(pp), 3)
+            res["ideal_attn_speedup"] = round(allowed_pairs(pw) / allowed_pairs(wx), 3)
+            res["roofline_ms_mfma"] = round(rx.flops / (PEAK_BF16_TFLOPS * 1e12) * 1e3, 4)
+            res["roofline_ms_hbm"] = round(algorithmic_bytes(wx, wx.total_tokens) / (PEAK_HBM_GBS * 1e9) * 1e3, 4)
+            extras[name] = res
+            del rp
+            if rx is not run:
+                del rx
+            torch.cuda.empty_cache()
+        out["all_configs"] = extras
+        out["paper_context"] = "paper reports 1.1-1.5x (1.3-1.6x packed) end-to-end training speedup on 8xH100"
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(w, tens)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
