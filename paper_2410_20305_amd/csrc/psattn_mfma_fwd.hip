@@ -1,0 +1,141 @@
+// bf16 MFMA forward kernels for gfx950; layout and staging helpers are in psattn_mfma_common.h.
+#include "psattn_mfma_common.h"
+
+namespace psattn {
+namespace {
+using namespace mma;
+
+// ------------------------------------------------------------------ forward
+// grid: one workgroup per (q-tile of 128 queries, q-head); 4 waves x 32 queries.
+__global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
+    __shared__ __attribute__((aligned(16))) char sK[64 * kRowBytes];
+    __shared__ __attribute__((aligned(16))) char sV[64 * kRowBytes];
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, g = l >> 5;
+    const int T = a.meta.T, Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
+    const DeviceCsr& csr = a.meta.fwd;
+    // heads of one kv group are neighbours in launch order and share an XCD when Hkv == 8
+    const int kvh = blockIdx.x % Hkv, rest = blockIdx.x / Hkv;
+    const int h = kvh * G + rest % G, qt = csr.order[rest / G];
+    const int q_row = qt * 128 + 32 * w + c32;
+    const bool valid = q_row < T;
+    Tok4 tk = {kPadStart, 0, 0, 0};
+    if (valid) tk = a.meta.tok[q_row];
+
+    const uint16_t* Q = static_cast<const uint16_t*>(a.Q);
+    const uint16_t* K = static_cast<const uint16_t*>(a.K) + kvh * 128;
+    const uint16_t* V = static_cast<const uint16_t*>(a.V) + kvh * 128;
+    const size_t kv_stride = static_cast<size_t>(Hkv) * 128;
+
+    Frag8 qf[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+        qf[t].u = valid ? *reinterpret_cast<const uint4*>(Q + (static_cast<size_t>(q_row) * Hq + h) * 128 + 16 * t + 8 * g)
+                        : make_uint4(0, 0, 0, 0);
+
+    f32x16 o[4];
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
+    float m = -INFINITY, lsum = 0.f;
+    const float c = a.scale * kLog2e;
+
+    int e = csr.row_ptr[qt];
+    const int e_end = csr.row_ptr[qt + 1];
+    Stage pk, pv;
+    int ent = 0;
+    if (e < e_end) {
+        ent = csr.entry[e];
+        stage_load(pk, K, (ent >> 2) * 64, T, kv_stride, tid);
+        stage_load(pv, V, (ent >> 2) * 64, T, kv_stride, tid);
+    }
+    for (; e < e_end; ++e) {
+        const int k0 = (ent >> 2) * 64;
+        const bool full = (ent & 3) == PSATTN_TILE_FULL;
+        __syncthreads();
+        stage_store(pk, sK, tid);
+        stage_store(pv, sV, tid);
+        __syncthreads();
+        if (e + 1 < e_end) {
+            ent = csr.entry[e + 1];
+            stage_load(pk, K, (ent >> 2) * 64, T, kv_stride, tid);
+            stage_load(pv, V, (ent >> 2) * 64, T, kv_stride, tid);
+        }
+        // S^T = K Q^T : rows = keys, column = this lane's query
+        f32x16 s[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) s[kb] = mfma(lds_rows(sK, 32 * kb + c32, 2 * t + g), qf[t].v, s[kb]);
+        }
+        if (!full) {
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int j = k0 + 32 * kb + acc_row(i, g);
+                    const bool ok = j >= tk.s && j <= q_row && !(j >= tk.hole_lo && j < tk.hole_hi);
+                    s[kb][i] = ok ? s[kb][i] : -INFINITY;
+                }
+        }
+        float mx = s[0][0];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+        mx = fmaxf(mx, other_half(mx));
+        const float m_new = fmaxf(m, mx * c);
+        const float m_use = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+        m = m_new;
+        float psum = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c, -m_use));
+                psum += s[kb][i];
+            }
+        lsum = lsum * alpha + psum;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+        // O^T += V^T P^T
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int half = 0; half < 2; ++half) {
+                const bf16x8 pb = pack8(s[kb], half);
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+                    o[db] = mfma(lds_cols(sV, 32 * kb + 16 * half, 32 * db, l), pb, o[db]);
+            }
+    }
+    const float l_tot = lsum + other_half(lsum);
+    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+    if (valid) {
+        uint16_t* orow = static_cast<uint16_t*>(a.Oout) + (static_cast<size_t>(q_row) * Hq + h) * 128;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4)
+                store4(orow + 32 * db + 8 * i4 + 4 * g, o[db][4 * i4] * inv, o[db][4 * i4 + 1] * inv,
+                       o[db][4 * i4 + 2] * inv, o[db][4 * i4 + 3] * inv);
+        if (g == 0)
+            a.LSEout[static_cast<size_t>(h) * T + q_row] = l_tot > 0.f ? m * kLn2 + __logf(l_tot) : -INFINITY;
+    }
+}
+
+}  // namespace
+
+int launch_mfma_fwd(const AttnArgs& a, void* stream) {
+    const unsigned grid = static_cast<unsigned>(a.meta.fwd.n_rows) * a.Hq;
+    if (grid == 0) return 0;
+    psattn_fwd_bf16_mfma<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(a);
+    return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace psattn
