@@ -8,7 +8,6 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
-#include <numeric>
 
 #include "psattn_internal.h"
 
@@ -111,14 +110,17 @@ void transpose(const TileCsr& in, TileCsr& out) {
         }
 }
 
-// Longest rows first, so the tail of a launch is made of short work items.
-void order_rows(TileCsr& g) {
+// Launch order of the rows.  Rows of one sample that are neighbours in this order run
+// at the same time and stream the same tiles of the other operand, so they should
+// stay neighbours (the L2 of an XCD then serves most of their reads); and inside a
+// sample the long rows should come first so the tail of the launch is short work.
+// Causality gives both: a q-tile late in its sample has the longest k-list, a k-tile
+// early in its sample the longest q-list.  So q-major rows run from the last tile to
+// the first, k-major rows from the first to the last.
+void order_rows(TileCsr& g, bool descending) {
     const int32_t n = static_cast<int32_t>(g.row_ptr.size()) - 1;
     g.order.resize(n);
-    std::iota(g.order.begin(), g.order.end(), 0);
-    std::stable_sort(g.order.begin(), g.order.end(), [&](int32_t x, int32_t y) {
-        return g.row_ptr[x + 1] - g.row_ptr[x] > g.row_ptr[y + 1] - g.row_ptr[y];
-    });
+    for (int32_t i = 0; i < n; ++i) g.order[i] = descending ? n - 1 - i : i;
 }
 
 }  // namespace
@@ -170,11 +172,11 @@ int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_l
             }
         }
         classify(samples, T, tile_q, tile_k, m->fwd);
-        order_rows(m->fwd);
+        order_rows(m->fwd, true);
         TileCsr qmajor;
         classify(samples, T, bwd_tile_q, bwd_tile_k, qmajor);
         transpose(qmajor, m->bwd);
-        order_rows(m->bwd);
+        order_rows(m->bwd, false);
         *out = m;
     } catch (const std::bad_alloc&) {
         return PSATTN_ENOMEM;

@@ -278,46 +278,74 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
 
     const int e0 = csr.row_ptr[kt], n_ent = csr.row_ptr[kt + 1] - e0;
     const int n_it = n_ent * G;
+
+    // Staging of one q-tile (64 rows x 256 B of Q and of dO, 64 LSE, 64 delta):
+    // thread tid moves 16-byte chunk (tid & 15) of rows (tid >> 4) + 16 i, i < 4.
+    // Rows past the end of the buffer re-read the last token: whatever they hold is
+    // removed by the pair masks (a clipped tile is never FULL).
+    const int st_row = tid >> 4, st_ch = tid & 15;
+    const int st_lds = tile_off(st_row, st_ch);  // + 16 i rows: the swizzle repeats every 16 rows
+    const uint32_t row_bytes = static_cast<uint32_t>(Hq) * 256u;
     Stage pq, pg;
     float pstat = 0.f;  // threads 0..63: LSE of query tid; 64..127: delta of query tid - 64
-    int ent_next = 0;
-    // Rows past the end of the buffer are read from the last token instead: whatever
-    // they hold is removed by the pair masks (a clipped tile is never FULL).
-    auto prefetch = [&](int it) {  // global -> registers
-        ent_next = csr.entry[e0 + it % n_ent];
-        const int h = kvh * G + it / n_ent;
-        const int q0 = (ent_next >> 2) * 64;
-        stage_load_clamped(pq, static_cast<const uint16_t*>(a.Q) + h * 128, q0, T, q_stride, tid);
-        stage_load_clamped(pg, static_cast<const uint16_t*>(a.dO) + h * 128, q0, T, q_stride, tid);
-        const int qi = min(q0 + (tid & 63), T - 1);
-        const float* src = (tid & 64) ? a.delta : a.LSE;
-        pstat = src[static_cast<size_t>(h) * T + qi] * ((tid & 64) ? 1.f : kLog2e);
+    auto prefetch = [&](int ent, int h) {  // global -> registers; nothing here waits for the data
+        const int q0 = (ent >> 2) * 64;
+        const size_t tile_elems = (static_cast<size_t>(q0) * Hq + h) * 128;
+        const char* qb = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.Q) + tile_elems);
+        const char* gb = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems);
+        const int rmax = T - 1 - q0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t off = static_cast<uint32_t>(min(st_row + 16 * i, rmax)) * row_bytes + st_ch * 16;
+            pq.c[i] = *reinterpret_cast<const u32x4*>(qb + off);
+            pg.c[i] = *reinterpret_cast<const u32x4*>(gb + off);
+        }
+        const float* src = ((tid & 64) ? a.delta : a.LSE) + static_cast<size_t>(h) * T + q0;
+        pstat = src[min(tid & 63, rmax)];
     };
     auto commit = [&](int buf) {  // registers -> LDS
-        stage_store(pq, sQ[buf], tid);
-        stage_store(pg, sG[buf], tid);
-        if (tid < 128) ((tid & 64) ? sD[buf] : sL[buf])[tid & 63] = pstat;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            *reinterpret_cast<u32x4*>(sQ[buf] + st_lds + 16 * i * kRowBytes) = pq.c[i];
+            *reinterpret_cast<u32x4*>(sG[buf] + st_lds + 16 * i * kRowBytes) = pg.c[i];
+        }
+        if (tid < 128) ((tid & 64) ? sD[buf] : sL[buf])[tid & 63] = pstat * ((tid & 64) ? 1.f : kLog2e);
     };
-    int ent = 0;
+    // Walk order: q-tiles from the last to the first, and for each q-tile the G heads
+    // of the group.  Every k-tile of a sample ends at the same q-tile, so workgroups
+    // of neighbouring k-tiles (which run at the same time on the same XCD) read the
+    // same Q / dO tile at the same moment and share it through L2.
+    // Tile list entries are fetched one tile ahead of the loads that need them, so no
+    // address ever waits on a load issued in the same iteration.
+    int pe = n_ent - 1, ph = 0;  // list position and head (within the group) of the next entry
+    auto next_entry = [&]() {
+        const int v = csr.entry[e0 + pe];
+        if (++ph == G) { ph = 0; --pe; }
+        return v;
+    };
+    int ent0 = 0, ent1 = 0, ent2 = 0, h2 = 0;  // entries of tiles it, it + 1, it + 2; head of tile it + 2
     if (n_it > 0) {
-        prefetch(0);
-        ent = ent_next;
+        ent0 = next_entry();
+        prefetch(ent0, kvh * G);
         commit(0);
-        if (n_it > 1) prefetch(1);
+        if (n_it > 1) { h2 = kvh * G + ph; ent1 = next_entry(); prefetch(ent1, h2); }
+        if (n_it > 2) { h2 = kvh * G + ph; ent2 = next_entry(); }
     }
     for (int it = 0; it < n_it; ++it) {
         const int buf = it & 1;
         // tile `it` was written before this barrier; tile it - 1 (same buffer as it + 1) is no longer read
         __syncthreads();
-        const int ent_cur = ent;
         if (it + 1 < n_it) {
-            ent = ent_next;
             commit(buf ^ 1);
-            if (it + 2 < n_it) prefetch(it + 2);
+            if (it + 2 < n_it) prefetch(ent2, h2);
         }
-        const int q0 = (ent_cur >> 2) * 64;
+        const int q0 = (ent0 >> 2) * 64;
+        const bool full = (ent0 & 3) == PSATTN_TILE_FULL;
+        ent0 = ent1;
+        ent1 = ent2;
+        if (it + 3 < n_it) { h2 = kvh * G + ph; ent2 = next_entry(); }
         uint32_t mw[2][8];
-        pair_masks(mw, (ent_cur & 3) == PSATTN_TILE_FULL, key - q0, key_hi - q0, g);
+        pair_masks(mw, full, key - q0, key_hi - q0, g);
         dkdv_tile(sQ[buf], sG[buf], sL[buf], sD[buf], lo, kf, vf, dk, dv, mw, c, g);
     }
     if (kvalid) {

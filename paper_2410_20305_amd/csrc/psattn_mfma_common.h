@@ -87,6 +87,28 @@ __device__ inline bf16x8 lds_cols(const char* tile, int row0, int col0, int l) {
     return f.v;
 }
 
+// per-lane LDS byte offsets that do not change over the kernel
+struct LaneOffsets {
+    int nat[8];  // row (l % 32), 16-byte chunk 2t + l / 32
+    int tr1[4];  // transposed operand of head-dim block db: rows 4 (l / 32) + ..., first four
+    int tr2[4];  // the same eight rows further down
+};
+
+__device__ inline LaneOffsets lane_offsets(int l) {
+    LaneOffsets o;
+    const int c32 = l & 31, g = l >> 5, i16 = l & 15;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) o.nat[t] = tile_off(c32, 2 * t + g);
+    const int row = 4 * g + (i16 >> 2);
+#pragma unroll
+    for (int db = 0; db < 4; ++db) {
+        const int col = 32 * db + 16 * ((l >> 4) & 1) + 4 * (i16 & 3);
+        o.tr1[db] = tile_off(row, col >> 3) + (col & 7) * 2;
+        o.tr2[db] = tile_off(row + 8, col >> 3) + (col & 7) * 2;
+    }
+    return o;
+}
+
 __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

@@ -39,6 +39,8 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         for (int i = 0; i < 16; ++i) o[db][i] = 0.f;
     float m = -INFINITY, lsum = 0.f;
     const float c = a.scale * kLog2e;
+    const LaneOffsets lo = lane_offsets(l);
+    constexpr int kAhead = 3, kRing = 4;
 
     int e = csr.row_ptr[qt];
     const int e_end = csr.row_ptr[qt + 1];
@@ -61,15 +63,34 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
             stage_load(pk, K, (ent >> 2) * 64, T, kv_stride, tid);
             stage_load(pv, V, (ent >> 2) * 64, T, kv_stride, tid);
         }
-        // S^T = K Q^T : rows = keys, column = this lane's query
+        // 32 MFMA slots per tile: 0-15 S^T = K Q^T (rows = keys, column = this lane's
+        // query), 16-31 O^T += V^T P^T.  The LDS operand of slot m is requested kAhead
+        // slots earlier into a register ring.
+        Frag8 ring[kRing];
+        auto request = [&](auto M) {
+            constexpr int m = decltype(M)::value;
+            if constexpr (m < 16) {
+                constexpr int t = m >> 1, kb = m & 1;
+                ring[m % kRing].v = *reinterpret_cast<const bf16x8*>(sK + lo.nat[t] + kb * 32 * kRowBytes);
+            } else if constexpr (m < 32) {
+                constexpr int j = m - 16, kb = j >> 3, half = (j >> 2) & 1, db = j & 3;
+                constexpr int base = (32 * kb + 16 * half) * kRowBytes;
+                ring[m % kRing].h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(sV + lo.tr1[db] + base));
+                ring[m % kRing].h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(sV + lo.tr2[db] + base));
+            }
+        };
         f32x16 s[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int i = 0; i < 16; ++i) s[kb][i] = 0.f;
-#pragma unroll
-            for (int t = 0; t < 8; ++t) s[kb] = mfma(lds_rows(sK, 32 * kb + c32, 2 * t + g), qf[t].v, s[kb]);
-        }
+        static_for<0, kAhead>([&](auto M) { request(M); });
+        static_for<0, 16>([&](auto M) {
+            constexpr int m = decltype(M)::value, t = m >> 1, kb = m & 1;
+            request(std::integral_constant<int, m + kAhead>{});
+            s[kb] = mfma(ring[m % kRing].v, qf[t].v, s[kb]);
+            __builtin_amdgcn_sched_barrier(0);
+        });
         if (!full) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
@@ -88,31 +109,36 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         mx = fmaxf(mx, other_half(mx));
         const float m_new = fmaxf(m, mx * c);
         const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-        m = m_new;
-        float psum = 0.f;
+        // the running maximum rarely moves once a row has seen many keys: rescale only then
+        if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {
+            const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+            lsum *= alpha;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
+            m = m_new;
+        }
+        float psum = 0.f;
+        bf16x8 pb[2][2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c, -m_use));
                 psum += s[kb][i];
             }
-        lsum = lsum * alpha + psum;
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
-        // O^T += V^T P^T
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const bf16x8 pb = pack8(s[kb], half);
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-                    o[db] = mfma(lds_cols(sV, 32 * kb + 16 * half, 32 * db, l), pb, o[db]);
-            }
+            pb[kb][0] = pack8(s[kb], 0);
+            pb[kb][1] = pack8(s[kb], 1);
+        }
+        lsum += psum;
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<16, 32>([&](auto M) {
+            constexpr int m = decltype(M)::value, j = m - 16, kb = j >> 3, half = (j >> 2) & 1, db = j & 3;
+            request(std::integral_constant<int, m + kAhead>{});
+            o[db] = mfma(ring[m % kRing].v, pb[kb][half], o[db]);
+            __builtin_amdgcn_sched_barrier(0);
+        });
     }
     const float l_tot = lsum + other_half(lsum);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
