@@ -222,13 +222,13 @@ int psattn_bwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.LSE = LSE;
     a.dQ = dQ; a.dK = dK; a.dV = dV;
     a.delta = reinterpret_cast<float*>(align_up(reinterpret_cast<uintptr_t>(workspace), 256));
-    int err;
-    {
+    int err = 0;
+    const bool mfma = mfma_bwd_ok(meta, dt, head_dim, scale);
+    if (!mfma) {  // the MFMA dQ kernel computes delta itself and leaves it in the workspace
         PassTimer t(1, hip_stream);
         err = launch_delta(dt, a, hip_stream);
     }
     if (err) return PSATTN_EHIP;
-    const bool mfma = mfma_bwd_ok(meta, dt, head_dim, scale);
     {
         PassTimer t(2, hip_stream);
         err = mfma ? launch_mfma_dq(a, hip_stream) : launch_generic_dq(dt, a, hip_stream);

@@ -14,6 +14,8 @@
 namespace psattn {
 namespace {
 
+constexpr int32_t kSmallGridRows = 256;
+
 inline int64_t tri(int64_t n) { return n * (n + 1) / 2; }
 
 // #{(q, k): qa <= q < qb, ka <= k < kb, k <= q}
@@ -110,17 +112,25 @@ void transpose(const TileCsr& in, TileCsr& out) {
         }
 }
 
-// Launch order of the rows.  Rows of one sample that are neighbours in this order run
-// at the same time and stream the same tiles of the other operand, so they should
-// stay neighbours (the L2 of an XCD then serves most of their reads); and inside a
-// sample the long rows should come first so the tail of the launch is short work.
-// Causality gives both: a q-tile late in its sample has the longest k-list, a k-tile
-// early in its sample the longest q-list.  So q-major rows run from the last tile to
-// the first, k-major rows from the first to the last.
+// Launch order of the rows.
+//
+// Large grids: rows of one sample that are neighbours in this order run at the same
+// time and stream the same tiles of the other operand, so they should stay
+// neighbours (the L2 of an XCD then serves most of their reads), and inside a sample
+// the long rows should come first.  Causality gives both: a q-tile late in its sample
+// has the longest k-list, a k-tile early in its sample the longest q-list.  So q-major
+// rows run from the last tile to the first, k-major rows from the first to the last.
+//
+// Small grids (fewer rows than a couple of waves of workgroups): there is little to
+// share and the tail dominates, so rows are simply sorted longest first.
 void order_rows(TileCsr& g, bool descending) {
     const int32_t n = static_cast<int32_t>(g.row_ptr.size()) - 1;
     g.order.resize(n);
     for (int32_t i = 0; i < n; ++i) g.order[i] = descending ? n - 1 - i : i;
+    if (n < kSmallGridRows)
+        std::stable_sort(g.order.begin(), g.order.end(), [&](int32_t x, int32_t y) {
+            return g.row_ptr[x + 1] - g.row_ptr[x] > g.row_ptr[y + 1] - g.row_ptr[y];
+        });
 }
 
 }  // namespace

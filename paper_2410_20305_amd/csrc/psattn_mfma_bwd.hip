@@ -34,7 +34,24 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     }
     // rows without keys (padding) keep LSE = -inf; every pair of theirs is masked below
     const float lse2 = valid ? a.LSE[static_cast<size_t>(h) * T + q_row] * kLog2e : INFINITY;
-    const float dl = valid ? a.delta[static_cast<size_t>(h) * T + q_row] : 0.f;
+    // delta = rowsum(dO o O): this lane holds half of the row's dO already, O is read once
+    // here; the result also goes to the workspace for the dK/dV pass that follows
+    float dl = 0.f;
+    if (valid) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const uint4 ov = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.O) + qoff + 16 * t + 8 * g);
+            const uint32_t ow[4] = {ov.x, ov.y, ov.z, ov.w};
+            const uint32_t gw[4] = {gf[t].u.x, gf[t].u.y, gf[t].u.z, gf[t].u.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                dl = fmaf(__uint_as_float(ow[j] << 16), __uint_as_float(gw[j] << 16), dl);
+                dl = fmaf(__uint_as_float(ow[j] & 0xffff0000u), __uint_as_float(gw[j] & 0xffff0000u), dl);
+            }
+        }
+    }
+    dl += other_half(dl);
+    if (valid && g == 0) a.delta[static_cast<size_t>(h) * T + q_row] = dl;
     const float c = a.scale * kLog2e;
 
     f32x16 dq[4];
