@@ -162,6 +162,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations and the paired baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="run a plain 1 GiB device copy 5 times and exit (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path "
@@ -178,6 +180,15 @@ def main():
         sys.exit(3)
     ps.load_library()
     torch.cuda.set_device(0)
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4,
+                          "launches": 5}))
+        return
 
     w = W.make_workload(args.workload)
     tens = W.make_tensors(w)
@@ -194,8 +205,18 @@ def main():
     dom = max((0, 2, 3), key=lambda i: per_pass[i])
     n_allowed = allowed_pairs(w)
     ach = alg[dom] * w.head_dim * w.n_q_heads * n_allowed / (per_pass[dom] * 1e-3) / 1e12
+    # HBM bytes per launch of that kernel, from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE
+    # runs (already scaled by the copy-kernel calibration); null for a workload not profiled
+    traffic = None
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")) as f:
+            t = json.load(f).get("%s/%s" % (args.workload, ps.psattn_kernel_name(1, dom)))
+        if t:
+            traffic = int(t["read_bytes"] + t["write_bytes"])
+    except (OSError, ValueError):
+        pass
     roofline = dict(bound="mfma", kernel=ps.psattn_kernel_name(1, dom), achieved=round(ach, 2),
-                    peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=None,
+                    peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=traffic,
                     avg_launch_ms=round(per_pass[dom], 4),
                     algorithmic_flops_per_launch=alg[dom] * w.head_dim * w.n_q_heads * n_allowed)
 
