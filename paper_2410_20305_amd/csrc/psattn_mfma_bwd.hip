@@ -137,28 +137,6 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
 // The LDS operand of slot m is requested kAhead slots earlier into a register
 // ring; q-tiles are double buffered in LDS with one barrier per tile.
 
-// per-lane LDS byte offsets that do not change over the kernel
-struct LaneOffsets {
-    int nat[8];  // row (l % 32), 16-byte chunk 2t + l / 32
-    int tr1[4];  // transposed operand of head-dim block db: rows 4 (l / 32) + ..., first four
-    int tr2[4];  // the same eight rows further down
-};
-
-__device__ inline LaneOffsets lane_offsets(int l) {
-    LaneOffsets o;
-    const int c32 = l & 31, g = l >> 5, i16 = l & 15;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) o.nat[t] = tile_off(c32, 2 * t + g);
-    const int row = 4 * g + (i16 >> 2);
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-        const int col = 32 * db + 16 * ((l >> 4) & 1) + 4 * (i16 & 3);
-        o.tr1[db] = tile_off(row, col >> 3) + (col & 7) * 2;
-        o.tr2[db] = tile_off(row + 8, col >> 3) + (col & 7) * 2;
-    }
-    return o;
-}
-
 constexpr int kQTileBytes = 64 * kRowBytes;
 constexpr int kAhead = 5;
 
@@ -213,13 +191,11 @@ __device__ __forceinline__ void dkdv_tile(const char* sQ, const char* sG, const 
         if constexpr (m < 32) {
             constexpr int b = m >> 4, t = (m & 15) >> 1;
             const char* x = (m & 1) ? sG : sQ;
-            ring[m & 7].v = *reinterpret_cast<const bf16x8*>(x + lo.nat[t] + b * 32 * kRowBytes);
+            ring[m & 7].v = ld_rows<t>(x + b * 32 * kRowBytes, lo.nat);
         } else if constexpr (m < 64) {
             constexpr int j = (m - 32) & 15, b = (m - 32) >> 4, half = j >> 3, db = (j & 7) >> 1;
             const char* x = (j & 1) ? sQ : sG;
-            constexpr int base = (32 * b + 16 * half) * kRowBytes;
-            ring[m & 7].h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(x + lo.tr1[db] + base));
-            ring[m & 7].h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(x + lo.tr2[db] + base));
+            ring[m & 7].v = ld_cols<db, half>(x + 32 * b * kRowBytes, lo.tr1, lo.tr2);
         }
     };
     auto stats = [&](int b, int i4, float4& L, float4& D) {  // LSE, delta of 4 consecutive queries

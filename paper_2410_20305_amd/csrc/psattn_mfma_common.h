@@ -87,26 +87,42 @@ __device__ inline bf16x8 lds_cols(const char* tile, int row0, int col0, int l) {
     return f.v;
 }
 
-// per-lane LDS byte offsets that do not change over the kernel
+// Per-lane LDS byte offsets of the two operand fetch patterns, relative to the first
+// row of a 32-row block.  Because the swizzle is an XOR on the 16-byte chunk index,
+// the offset for step t (row-wise operand) or head-dim block db (transposed operand)
+// is one lane constant XOR a compile-time constant:
+//   row-wise, step t:        nat ^ (t << 5)     row l % 32, chunk 2 t + l / 32
+//   transposed, block db:    tr1 ^ (db << 6)    rows 4 (l / 32) + (l % 16) / 4, first four
+//                            tr2 ^ (db << 6)    the same, eight rows further down
+// A tile base that is a multiple of 256 bytes may be added to the lane constant first.
 struct LaneOffsets {
-    int nat[8];  // row (l % 32), 16-byte chunk 2t + l / 32
-    int tr1[4];  // transposed operand of head-dim block db: rows 4 (l / 32) + ..., first four
-    int tr2[4];  // the same eight rows further down
+    int nat, tr1, tr2;
 };
 
 __device__ inline LaneOffsets lane_offsets(int l) {
     LaneOffsets o;
     const int c32 = l & 31, g = l >> 5, i16 = l & 15;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) o.nat[t] = tile_off(c32, 2 * t + g);
+    o.nat = tile_off(c32, g);
     const int row = 4 * g + (i16 >> 2);
-#pragma unroll
-    for (int db = 0; db < 4; ++db) {
-        const int col = 32 * db + 16 * ((l >> 4) & 1) + 4 * (i16 & 3);
-        o.tr1[db] = tile_off(row, col >> 3) + (col & 7) * 2;
-        o.tr2[db] = tile_off(row + 8, col >> 3) + (col & 7) * 2;
-    }
+    const int col = 16 * ((l >> 4) & 1) + 4 * (i16 & 3);
+    o.tr1 = tile_off(row, col >> 3) + (col & 7) * 2;
+    o.tr2 = tile_off(row + 8, col >> 3) + (col & 7) * 2;
     return o;
+}
+
+// row-wise MFMA operand, step t, of the 32-row block at `blk` (blk: multiple of 256 bytes)
+template <int T>
+__device__ __forceinline__ bf16x8 ld_rows(const char* blk, int nat) {
+    return *reinterpret_cast<const bf16x8*>(blk + (nat ^ (T << 5)));
+}
+
+// transposed MFMA operand: head-dim block DB, stored rows 16 HALF + {0..15} of the block
+template <int DB, int HALF>
+__device__ __forceinline__ bf16x8 ld_cols(const char* blk, int tr1, int tr2) {
+    Frag8 f;
+    f.h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(blk + (tr1 ^ (DB << 6)) + 16 * HALF * kRowBytes));
+    f.h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(blk + (tr2 ^ (DB << 6)) + 16 * HALF * kRowBytes));
+    return f.v;
 }
 
 __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {

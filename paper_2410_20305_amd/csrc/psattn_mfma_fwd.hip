@@ -71,12 +71,10 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
             constexpr int m = decltype(M)::value;
             if constexpr (m < 16) {
                 constexpr int t = m >> 1, kb = m & 1;
-                ring[m % kRing].v = *reinterpret_cast<const bf16x8*>(sK + lo.nat[t] + kb * 32 * kRowBytes);
+                ring[m % kRing].v = ld_rows<t>(sK + kb * 32 * kRowBytes, lo.nat);
             } else if constexpr (m < 32) {
                 constexpr int j = m - 16, kb = j >> 3, half = (j >> 2) & 1, db = j & 3;
-                constexpr int base = (32 * kb + 16 * half) * kRowBytes;
-                ring[m % kRing].h[0] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(sV + lo.tr1[db] + base));
-                ring[m % kRing].h[1] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4*)(sV + lo.tr2[db] + base));
+                ring[m % kRing].v = ld_cols<db, half>(sV + 32 * kb * kRowBytes, lo.tr1, lo.tr2);
             }
         };
         f32x16 s[2];
