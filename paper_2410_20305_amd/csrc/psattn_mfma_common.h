@@ -150,6 +150,26 @@ __device__ inline float other_half(float x) {
 // row of the 32x32 accumulator that register i of lane-half g holds
 __device__ inline int acc_row(int i, int g) { return (i >> 2) * 8 + 4 * g + (i & 3); }
 
+// Asynchronous copy of a 64-row x 256-byte tile from global memory straight into a
+// swizzled LDS tile (global_load_lds_dwordx4: no staging registers, no ds_write).
+// A wave instruction writes 64 x 16 bytes to consecutive LDS addresses in lane order
+// = four tile rows, so the swizzle is applied on the global side: lane l fetches the
+// logical chunk that belongs at physical chunk l % 16 of row r4 + l / 16.  Each of the
+// four waves of a workgroup copies 16 rows.  `base` points at row `row0` ... the tile's
+// rows are `row_bytes` apart; rows past `last_row` (relative to row0) re-read that row.
+// Completion is tracked by vmcnt; __syncthreads() waits for it.
+__device__ __forceinline__ void dma_tile64(const char* base, uint32_t row_bytes, int last_row, char* tile, int w, int l) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int r4 = 16 * w + 4 * i;
+        const int row = r4 + (l >> 4);
+        const int sw = ((row & 3) << 2) | ((row >> 2) & 3);
+        const char* src = base + static_cast<uint32_t>(min(row, last_row)) * row_bytes + (((l & 15) ^ sw) << 4);
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                         (__attribute__((address_space(3))) void*)(tile + r4 * kRowBytes), 16, 0, 0);
+    }
+}
+
 struct Stage {  // one thread's share of a 64 x 128 bf16 tile: 4 chunks of 16 bytes
     u32x4 c[4];
 };

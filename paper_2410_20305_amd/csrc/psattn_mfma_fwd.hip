@@ -8,8 +8,8 @@ using namespace mma;
 // ------------------------------------------------------------------ forward
 // grid: one workgroup per (q-tile of 128 queries, q-head); 4 waves x 32 queries.
 __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
-    __shared__ __attribute__((aligned(16))) char sK[64 * kRowBytes];
-    __shared__ __attribute__((aligned(16))) char sV[64 * kRowBytes];
+    __shared__ __attribute__((aligned(16))) char sKb[2][64 * kRowBytes];  // double buffered
+    __shared__ __attribute__((aligned(16))) char sVb[2][64 * kRowBytes];
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, g = l >> 5;
     const int T = a.meta.T, Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
     const DeviceCsr& csr = a.meta.fwd;
@@ -42,27 +42,36 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
     const LaneOffsets lo = lane_offsets(l);
     constexpr int kAhead = 3, kRing = 4;
 
+    // K / V tiles are copied global -> LDS asynchronously, one tile ahead, into the
+    // buffer the previous tile has just vacated; one barrier per tile.
+    const uint32_t row_bytes = static_cast<uint32_t>(Hkv) * 256u;
+    const char* Kb = reinterpret_cast<const char*>(K);
+    const char* Vb = reinterpret_cast<const char*>(V);
+    auto fetch = [&](int ent, int buf) {
+        const int k0 = (ent >> 2) * 64;
+        dma_tile64(Kb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sKb[buf], w, l);
+        dma_tile64(Vb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sVb[buf], w, l);
+    };
     int e = csr.row_ptr[qt];
     const int e_end = csr.row_ptr[qt + 1];
-    Stage pk, pv;
-    int ent = 0;
+    int ent = 0, ent_next = 0, buf = 0;
     if (e < e_end) {
         ent = csr.entry[e];
-        stage_load(pk, K, (ent >> 2) * 64, T, kv_stride, tid);
-        stage_load(pv, V, (ent >> 2) * 64, T, kv_stride, tid);
+        fetch(ent, 0);
+        if (e + 1 < e_end) ent_next = csr.entry[e + 1];
     }
-    for (; e < e_end; ++e) {
+    for (; e < e_end; ++e, buf ^= 1) {
         const int k0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
-        __syncthreads();
-        stage_store(pk, sK, tid);
-        stage_store(pv, sV, tid);
+        // this tile has landed (vmcnt) and every wave has left the other buffer
         __syncthreads();
         if (e + 1 < e_end) {
-            ent = csr.entry[e + 1];
-            stage_load(pk, K, (ent >> 2) * 64, T, kv_stride, tid);
-            stage_load(pv, V, (ent >> 2) * 64, T, kv_stride, tid);
+            fetch(ent_next, buf ^ 1);
+            ent = ent_next;
+            if (e + 2 < e_end) ent_next = csr.entry[e + 2];
         }
+        const char* sK = sKb[buf];
+        const char* sV = sVb[buf];
         // 32 MFMA slots per tile: 0-15 S^T = K Q^T (rows = keys, column = this lane's
         // query), 16-31 O^T += V^T P^T.  The LDS operand of slot m is requested kAhead
         // slots earlier into a register ring.
