@@ -161,7 +161,7 @@ int psattn_fwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n
  * queries.  The paper times forward and backward together (Section 4.2).
  *
  * workspace: device scratch of at least psattn_bwd_workspace_bytes() bytes, owned by
- * the caller, contents undefined on entry and exit (holds delta).
+ * the caller, contents undefined on entry and exit (holds delta and a rescaled copy of LSE).
  */
 int psattn_bwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
                int32_t head_dim, float scale,

@@ -204,7 +204,7 @@ size_t psattn_bwd_workspace_bytes(const psattn_meta* meta, int32_t n_q_heads, in
                                   int32_t head_dim) {
     (void)n_kv_heads; (void)head_dim;
     if (!meta || n_q_heads <= 0) return 0;
-    return align_up(sizeof(float) * static_cast<size_t>(meta->T) * n_q_heads, 256) + 256;
+    return 2 * align_up(sizeof(float) * static_cast<size_t>(meta->T) * n_q_heads, 256) + 256;
 }
 
 int psattn_bwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
@@ -222,6 +222,7 @@ int psattn_bwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.LSE = LSE;
     a.dQ = dQ; a.dK = dK; a.dV = dV;
     a.delta = reinterpret_cast<float*>(align_up(reinterpret_cast<uintptr_t>(workspace), 256));
+    a.lse2 = a.delta + align_up(sizeof(float) * static_cast<size_t>(meta->T) * n_q_heads, 256) / sizeof(float);
     int err = 0;
     const bool mfma = mfma_bwd_ok(meta, dt, head_dim, scale);
     if (!mfma) {  // the MFMA dQ kernel computes delta itself and leaves it in the workspace

@@ -81,7 +81,8 @@ struct AttnArgs {
     const float* LSE;
     void *Oout, *dQ, *dK, *dV;
     float* LSEout;
-    float* delta;  // [Hq, T]
+    float* delta;  // [Hq, T]  workspace: rowsum(dO o O)
+    float* lse2;   // [Hq, T]  workspace: LSE * log2(e), written by the MFMA dQ pass for the dK/dV pass
 };
 
 // Launchers (each returns a hipError_t cast to int; 0 = success).

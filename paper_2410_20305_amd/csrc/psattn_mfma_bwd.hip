@@ -50,7 +50,10 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
         }
     }
     dl += other_half(dl);
-    if (valid && g == 0) a.delta[static_cast<size_t>(h) * T + q_row] = dl;
+    if (valid && g == 0) {
+        a.delta[static_cast<size_t>(h) * T + q_row] = dl;
+        a.lse2[static_cast<size_t>(h) * T + q_row] = lse2;
+    }
     const float c = a.scale * kLog2e;
 
     f32x16 dq[4];
@@ -278,37 +281,23 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
     const int e0 = csr.row_ptr[kt], n_ent = csr.row_ptr[kt + 1] - e0;
     const int n_it = n_ent * G;
 
-    // Staging of one q-tile (64 rows x 256 B of Q and of dO, 64 LSE, 64 delta):
-    // thread tid moves 16-byte chunk (tid & 15) of rows (tid >> 4) + 16 i, i < 4.
-    // Rows past the end of the buffer re-read the last token: whatever they hold is
-    // removed by the pair masks (a clipped tile is never FULL).
-    const int st_row = tid >> 4, st_ch = tid & 15;
-    const int st_lds = tile_off(st_row, st_ch);  // + 16 i rows: the swizzle repeats every 16 rows
+    // Staging of one q-tile (64 rows x 256 B of Q and of dO, 64 LSE * log2 e, 64 delta):
+    // asynchronous global -> LDS copies, issued one tile ahead into the buffer the
+    // previous tile has just vacated.  Rows past the end of the buffer re-read the
+    // last token: whatever they hold is removed by the pair masks (a clipped tile is
+    // never FULL).
     const uint32_t row_bytes = static_cast<uint32_t>(Hq) * 256u;
-    Stage pq, pg;
-    float pstat = 0.f;  // threads 0..63: LSE of query tid; 64..127: delta of query tid - 64
-    auto prefetch = [&](int ent, int h) {  // global -> registers; nothing here waits for the data
+    auto prefetch = [&](int ent, int h, int buf) {
         const int q0 = (ent >> 2) * 64;
         const size_t tile_elems = (static_cast<size_t>(q0) * Hq + h) * 128;
-        const char* qb = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.Q) + tile_elems);
-        const char* gb = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems);
         const int rmax = T - 1 - q0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t off = static_cast<uint32_t>(min(st_row + 16 * i, rmax)) * row_bytes + st_ch * 16;
-            pq.c[i] = *reinterpret_cast<const u32x4*>(qb + off);
-            pg.c[i] = *reinterpret_cast<const u32x4*>(gb + off);
+        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.Q) + tile_elems), row_bytes, rmax, sQ[buf], w, l);
+        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems), row_bytes, rmax, sG[buf], w, l);
+        if (w < 2) {  // wave 0: 64 x LSE * log2 e, wave 1: 64 x delta, one dword per lane
+            const float* src = (w ? a.delta : a.lse2) + static_cast<size_t>(h) * T + q0 + min(l, rmax);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(w ? sD[buf] : sL[buf]), 4, 0, 0);
         }
-        const float* src = ((tid & 64) ? a.delta : a.LSE) + static_cast<size_t>(h) * T + q0;
-        pstat = src[min(tid & 63, rmax)];
-    };
-    auto commit = [&](int buf) {  // registers -> LDS
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            *reinterpret_cast<u32x4*>(sQ[buf] + st_lds + 16 * i * kRowBytes) = pq.c[i];
-            *reinterpret_cast<u32x4*>(sG[buf] + st_lds + 16 * i * kRowBytes) = pg.c[i];
-        }
-        if (tid < 128) ((tid & 64) ? sD[buf] : sL[buf])[tid & 63] = pstat * ((tid & 64) ? 1.f : kLog2e);
     };
     // Walk order: q-tiles from the last to the first, and for each q-tile the G heads
     // of the group.  Every k-tile of a sample ends at the same q-tile, so workgroups
@@ -322,27 +311,21 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
         if (++ph == G) { ph = 0; --pe; }
         return v;
     };
-    int ent0 = 0, ent1 = 0, ent2 = 0, h2 = 0;  // entries of tiles it, it + 1, it + 2; head of tile it + 2
+    int ent0 = 0, ent1 = 0, h1 = 0;  // entries of tiles it, it + 1; head of tile it + 1
     if (n_it > 0) {
         ent0 = next_entry();
-        prefetch(ent0, kvh * G);
-        commit(0);
-        if (n_it > 1) { h2 = kvh * G + ph; ent1 = next_entry(); prefetch(ent1, h2); }
-        if (n_it > 2) { h2 = kvh * G + ph; ent2 = next_entry(); }
+        prefetch(ent0, kvh * G, 0);
+        if (n_it > 1) { h1 = kvh * G + ph; ent1 = next_entry(); }
     }
     for (int it = 0; it < n_it; ++it) {
         const int buf = it & 1;
-        // tile `it` was written before this barrier; tile it - 1 (same buffer as it + 1) is no longer read
+        // tile `it` has landed (vmcnt) and tile it - 1 (same buffer as it + 1) is no longer read
         __syncthreads();
-        if (it + 1 < n_it) {
-            commit(buf ^ 1);
-            if (it + 2 < n_it) prefetch(ent2, h2);
-        }
+        if (it + 1 < n_it) prefetch(ent1, h1, buf ^ 1);
         const int q0 = (ent0 >> 2) * 64;
         const bool full = (ent0 & 3) == PSATTN_TILE_FULL;
         ent0 = ent1;
-        ent1 = ent2;
-        if (it + 3 < n_it) { h2 = kvh * G + ph; ent2 = next_entry(); }
+        if (it + 2 < n_it) { h1 = kvh * G + ph; ent1 = next_entry(); }
         uint32_t mw[2][8];
         pair_masks(mw, full, key - q0, key_hi - q0, g);
         dkdv_tile(sQ[buf], sG[buf], sL[buf], sD[buf], lo, kf, vf, dk, dv, mw, c, g);
