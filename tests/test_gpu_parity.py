@@ -174,3 +174,63 @@ def test_config5_sampled():
     tens = W.make_tensors(w)
     out, _ = run_gpu(w, tens)
     compare_subset(w, tens, out, samples=[4], kv_heads=[3], n_rows=32)
+
+
+@pytest.mark.parametrize("hq,hkv", [(1, 1), (3, 1), (6, 2), (16, 2)])
+def test_bf16_mfma_head_groupings(hq, hkv):
+    """MHA, odd and large query groups on the MFMA path (default grids)."""
+    w = W.custom_workload([(70, 33, 21), (140, 1, 66)], offsets=[0, 130], total_tokens=340, hq=hq, hkv=hkv,
+                          d=128, dtype="bf16", seed=61)
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    compare_full(w, tens, out, "bf16")
+
+
+def test_bf16_packed_rows_random():
+    """Packed rows with padding tails, lengths drawn like the packed configurations but small."""
+    rng = np.random.default_rng(71)
+    samples, offsets, row_len, rows = [], [], 700, 3
+    for r in range(rows):
+        fill = 0
+        while True:
+            s = tuple(int(x) for x in rng.integers(8, 120, 3))
+            if fill + sum(s) > row_len:
+                break
+            samples.append(s)
+            offsets.append(r * row_len + fill)
+            fill += sum(s)
+    w = W.custom_workload(samples, offsets=offsets, total_tokens=rows * row_len, hq=4, hkv=2, d=128,
+                          dtype="bf16", seed=72)
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    compare_full(w, tens, out, "bf16")
+
+
+def test_bf16_nonpositive_scale_uses_generic_kernels():
+    w = W.custom_workload([(40, 20, 30)], hq=2, hkv=1, d=128, dtype="bf16", seed=81, scale=-0.05)
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    compare_full(w, tens, out, "bf16")
+
+
+def test_api_errors_on_device():
+    import torch
+    w = W.custom_workload([(10, 4, 6)], hq=2, hkv=1, d=128, dtype="bf16", seed=91)
+    meta = ps.psattn_build_meta(w.offset, w.prefix_len, w.chosen_len, w.rejected_len, w.total_tokens)
+    q = torch.zeros((20, 2, 128), dtype=torch.bfloat16, device="cuda")
+    k = torch.zeros((20, 1, 128), dtype=torch.bfloat16, device="cuda")
+    o, lse = ps.psattn_fwd(meta, q, k, k, 0.1)
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(ps.PsattnError) as e:
+        ps.psattn_bwd(meta, q, k, k, o, q, lse, 0.1, workspace=small)
+    assert e.value.status == -1
+    with pytest.raises(ValueError):
+        ps.psattn_fwd(meta, q[:10], k, k, 0.1)           # wrong token count
+    with pytest.raises(TypeError):
+        ps.psattn_fwd(meta, q.half(), k.half(), k.half(), 0.1)
+    lib = ps.load_library()
+    assert lib.psattn_fwd(meta.handle, 1, 2, 1, 128, 0.1, q.data_ptr(), None, k.data_ptr(), o.data_ptr(),
+                          lse.data_ptr(), None) == -1   # null tensor
+    meta.free()
+    with pytest.raises(ValueError):
+        meta.handle
