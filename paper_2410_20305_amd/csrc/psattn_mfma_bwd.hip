@@ -9,7 +9,7 @@ using namespace mma;
 __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) char sKb[2][64 * kRowBytes];  // double buffered
     __shared__ __attribute__((aligned(16))) char sVb[2][64 * kRowBytes];
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, g = l >> 5;
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, c32 = l & 31, g = l >> 5;
     const int T = a.meta.T, Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
     const DeviceCsr& csr = a.meta.fwd;
     const int kvh = blockIdx.x % Hkv, rest = blockIdx.x / Hkv;
@@ -70,24 +70,28 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
         dma_tile64(reinterpret_cast<const char*>(K) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sKb[buf], w, l);
         dma_tile64(reinterpret_cast<const char*>(V) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sVb[buf], w, l);
     };
-    int e = csr.row_ptr[qt];
-    const int e_end = csr.row_ptr[qt + 1];
+    const int e0 = csr.row_ptr[qt], n_ent = csr.row_ptr[qt + 1] - e0;
+    EntryStream es;
+    es.init(csr.entry, e0, 1, n_ent, l);
     int ent = 0, ent_next = 0, buf = 0;
-    if (e < e_end) {
-        ent = csr.entry[e];
+    if (n_ent > 0) {
+        ent = es.get(0);
         fetch(ent, 0);
-        if (e + 1 < e_end) ent_next = csr.entry[e + 1];
     }
-    for (; e < e_end; ++e, buf ^= 1) {
+    // every compiler-tracked load and store above has retired before the loop starts, so
+    // the loop body holds no wait of the compiler's that would also cover copies in flight
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    for (int it = 0; it < n_ent; ++it, buf ^= 1) {
+        // this wave's copies of tile `it` have landed; after the barrier every wave's
+        // have, and every wave has left the other buffer
+        dma_wait_barrier<0>();
+        if (it + 1 < n_ent) {
+            ent_next = es.get(it + 1);
+            fetch(ent_next, buf ^ 1);
+        }
         const int k0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
-        // this tile has landed (vmcnt) and every wave has left the other buffer
-        __syncthreads();
-        if (e + 1 < e_end) {
-            fetch(ent_next, buf ^ 1);
-            ent = ent_next;
-            if (e + 2 < e_end) ent_next = csr.entry[e + 2];
-        }
+        ent = ent_next;
         const char* sK = sKb[buf];
         const char* sV = sVb[buf];
 #pragma unroll
@@ -252,7 +256,7 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) char sG[2][kQTileBytes];  // dO
     __shared__ __attribute__((aligned(16))) float sL[2][64];          // LSE * log2(e)
     __shared__ __attribute__((aligned(16))) float sD[2][64];          // delta
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, g = l >> 5;
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, c32 = l & 31, g = l >> 5;
     const int T = a.meta.T, Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
     const DeviceCsr& csr = a.meta.bwd;
     const int kvh = blockIdx.x % Hkv, kt = csr.order[blockIdx.x / Hkv];
@@ -295,37 +299,38 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
         dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems), row_bytes, rmax, sG[buf], w, l);
         if (w < 2) {  // wave 0: 64 x LSE * log2 e, wave 1: 64 x delta, one dword per lane
             const float* src = (w ? a.delta : a.lse2) + static_cast<size_t>(h) * T + q0 + min(l, rmax);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)(w ? sD[buf] : sL[buf]), 4, 0, 0);
+            dma4(src, lds_addr(w ? sD[buf] : sL[buf]));
         }
     };
     // Walk order: q-tiles from the last to the first, and for each q-tile the G heads
     // of the group.  Every k-tile of a sample ends at the same q-tile, so workgroups
     // of neighbouring k-tiles (which run at the same time on the same XCD) read the
     // same Q / dO tile at the same moment and share it through L2.
-    // Tile list entries are fetched one tile ahead of the loads that need them, so no
-    // address ever waits on a load issued in the same iteration.
-    int pe = n_ent - 1, ph = 0;  // list position and head (within the group) of the next entry
-    auto next_entry = [&]() {
-        const int v = csr.entry[e0 + pe];
-        if (++ph == G) { ph = 0; --pe; }
-        return v;
-    };
-    int ent0 = 0, ent1 = 0, h1 = 0;  // entries of tiles it, it + 1; head of tile it + 1
+    EntryStream es;
+    es.init(csr.entry, e0 + n_ent - 1, -1, n_ent, l);
+    int pk = 0, ph = 0;  // walk position and head (within the group) of the next tile
+    int ent0 = 0, ent1 = 0;
     if (n_it > 0) {
-        ent0 = next_entry();
+        ent0 = es.get(0);
         prefetch(ent0, kvh * G, 0);
-        if (n_it > 1) { h1 = kvh * G + ph; ent1 = next_entry(); }
+        if (++ph == G) { ph = 0; ++pk; }
     }
+    // K / V fragments are in registers before the loop starts, so the loop body holds no
+    // wait on a compiler-tracked load (such a wait would also cover the copies in flight)
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     for (int it = 0; it < n_it; ++it) {
         const int buf = it & 1;
-        // tile `it` has landed (vmcnt) and tile it - 1 (same buffer as it + 1) is no longer read
-        __syncthreads();
-        if (it + 1 < n_it) prefetch(ent1, h1, buf ^ 1);
+        // this wave's copies of tile `it` have landed; after the barrier every wave's
+        // have, and tile it - 1 (same buffer as it + 1) is no longer read
+        dma_wait_barrier<0>();
+        if (it + 1 < n_it) {
+            ent1 = es.get(pk);
+            prefetch(ent1, kvh * G + ph, buf ^ 1);
+            if (++ph == G) { ph = 0; ++pk; }
+        }
         const int q0 = (ent0 >> 2) * 64;
         const bool full = (ent0 & 3) == PSATTN_TILE_FULL;
         ent0 = ent1;
-        if (it + 2 < n_it) { h1 = kvh * G + ph; ent1 = next_entry(); }
         uint32_t mw[2][8];
         pair_masks(mw, full, key - q0, key_hi - q0, g);
         dkdv_tile(sQ[buf], sG[buf], sL[buf], sD[buf], lo, kf, vf, dk, dv, mw, c, g);

@@ -15,8 +15,8 @@
 //  * K/V (or Q/dO) tiles are staged in LDS, 256-byte rows, with the 16-byte chunk
 //    index XOR-swizzled by the row so that both row-wise 128-bit reads and the
 //    transposing 64-bit reads (ds_read_b64_tr_b16) are bank-conflict free without
-//    padding.  The next tile's global loads are issued before the current tile's
-//    math and parked in registers.
+//    padding.  Tiles are copied global -> LDS asynchronously, one tile ahead, into
+//    the buffer the previous tile has just vacated; one barrier per tile.
 //  * dK/dV are owned by one workgroup per (k-tile, kv-head), which walks the G
 //    query heads of the group and the k-major tile list, so the prompt's keys
 //    collect the contributions of prompt, chosen and rejected queries without
@@ -150,61 +150,81 @@ __device__ inline float other_half(float x) {
 // row of the 32x32 accumulator that register i of lane-half g holds
 __device__ inline int acc_row(int i, int g) { return (i >> 2) * 8 + 4 * g + (i & 3); }
 
-// Asynchronous copy of a 64-row x 256-byte tile from global memory straight into a
-// swizzled LDS tile (global_load_lds_dwordx4: no staging registers, no ds_write).
-// A wave instruction writes 64 x 16 bytes to consecutive LDS addresses in lane order
-// = four tile rows, so the swizzle is applied on the global side: lane l fetches the
+// Asynchronous global -> LDS copies (global_load_lds_*): no staging registers.
+// One wave instruction writes lane l's 16 (or 4) bytes at LDS base + 16 (4) * l, the
+// base being wave-uniform (M0).  The copies are issued from inline assembly on
+// purpose: the compiler's wait-count bookkeeping treats every LDS read that follows a
+// copy it knows of as dependent on it and waits for vmcnt(0) there, which would
+// serialise each copy with the arithmetic it is meant to overlap.  Completion is
+// therefore tracked by hand: copies retire in issue order, dma_wait_barrier<N>()
+// waits until at most N of this wave's copies are in flight and then joins the
+// workgroup barrier.  Compiler-issued vector memory loads stay correct (its waits can
+// only be stricter than needed); inside the tile loops there are none except the tile
+// list refills, which are consumed right after a full wait.
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) char*)p));
+}
+
+__device__ __forceinline__ void dma16(const void* src, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(src) : "memory");
+}
+
+__device__ __forceinline__ void dma4(const void* src, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(src) : "memory");
+}
+
+template <int N>
+__device__ __forceinline__ void dma_wait_barrier() {
+    asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
+}
+
+// Copy of a 64-row tile (256-byte rows) into a swizzled LDS tile.  A wave instruction
+// fills four tile rows, so the swizzle is applied on the global side: lane l fetches the
 // logical chunk that belongs at physical chunk l % 16 of row r4 + l / 16.  Each of the
-// four waves of a workgroup copies 16 rows.  `base` points at row `row0` ... the tile's
-// rows are `row_bytes` apart; rows past `last_row` (relative to row0) re-read that row.
-// Completion is tracked by vmcnt; __syncthreads() waits for it.
-__device__ __forceinline__ void dma_tile64(const char* base, uint32_t row_bytes, int last_row, char* tile, int w, int l) {
+// four waves of a workgroup copies 16 rows (4 copies per lane).  `base` points at the
+// tile's first row, rows are `row_bytes` apart; rows past `last_row` re-read that row.
+// `w` must be wave-uniform.
+__device__ __forceinline__ void dma_tile64(const char* base, uint32_t row_bytes, int last_row, const char* tile, int w, int l) {
+    const uint32_t lds = lds_addr(tile);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int r4 = 16 * w + 4 * i;
         const int row = r4 + (l >> 4);
         const int sw = ((row & 3) << 2) | ((row >> 2) & 3);
         const char* src = base + static_cast<uint32_t>(min(row, last_row)) * row_bytes + (((l & 15) ^ sw) << 4);
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                         (__attribute__((address_space(3))) void*)(tile + r4 * kRowBytes), 16, 0, 0);
+        dma16(src, lds + r4 * kRowBytes);
     }
 }
 
-struct Stage {  // one thread's share of a 64 x 128 bf16 tile: 4 chunks of 16 bytes
-    u32x4 c[4];
+// Reader of a tile list walked in one direction: position k = 0, 1, ... maps to
+// list[first + step * k] (step = +1 or -1), n positions in all.  Lane l keeps entry
+// 64 b + l of the current batch b; the next batch is requested when a batch is entered,
+// i.e. 64 positions before its first use.  get(k) must be called with non-decreasing k,
+// from wave-uniform control flow, at a point where no asynchronous copy is in flight
+// (the refill is a compiler-tracked load and is waited for with vmcnt(0)).
+struct EntryStream {
+    const int* list;
+    int first, step, n, l;
+    int cur, nxt, batch;
+    __device__ __forceinline__ int fetch(int b) const {
+        const int k = min(64 * b + l, n - 1);
+        return list[first + step * k];
+    }
+    __device__ __forceinline__ void init(const int* list_, int first_, int step_, int n_, int l_) {
+        list = list_; first = first_; step = step_; n = n_; l = l_;
+        batch = 0;
+        cur = n > 0 ? fetch(0) : 0;
+        nxt = n > 64 ? fetch(1) : 0;
+    }
+    __device__ __forceinline__ int get(int k) {
+        if ((k >> 6) != batch) {
+            batch = k >> 6;
+            cur = nxt;
+            if (64 * (batch + 1) < n) nxt = fetch(batch + 1);
+        }
+        return __builtin_amdgcn_readlane(cur, k & 63);
+    }
 };
-
-__device__ inline void stage_load(Stage& s, const uint16_t* base, int row0, int T, size_t row_stride,
-                                  int tid) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int idx = tid + 256 * i, row = idx >> 4, ch = idx & 15;
-        const int tok = row0 + row;
-        const u32x4 zero = {0u, 0u, 0u, 0u};
-        s.c[i] = tok < T ? *reinterpret_cast<const u32x4*>(base + static_cast<size_t>(tok) * row_stride + ch * 8)
-                         : zero;
-    }
-}
-
-// Same, but rows past the end of the buffer re-read the last token (no branch); the
-// caller masks whatever those rows produce.
-__device__ inline void stage_load_clamped(Stage& s, const uint16_t* base, int row0, int T, size_t row_stride,
-                                          int tid) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int idx = tid + 256 * i, row = idx >> 4, ch = idx & 15;
-        const int tok = min(row0 + row, T - 1);
-        s.c[i] = *reinterpret_cast<const u32x4*>(base + static_cast<size_t>(tok) * row_stride + ch * 8);
-    }
-}
-
-__device__ inline void stage_store(const Stage& s, char* tile, int tid) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int idx = tid + 256 * i, row = idx >> 4, ch = idx & 15;
-        *reinterpret_cast<u32x4*>(tile + tile_off(row, ch)) = s.c[i];
-    }
-}
 
 __device__ inline void store4(uint16_t* dst, float a, float b, float c, float d) {
     f32x2 v0 = {a, b}, v1 = {c, d};

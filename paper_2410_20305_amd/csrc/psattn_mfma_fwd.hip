@@ -10,7 +10,7 @@ using namespace mma;
 __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) char sKb[2][64 * kRowBytes];  // double buffered
     __shared__ __attribute__((aligned(16))) char sVb[2][64 * kRowBytes];
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, g = l >> 5;
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, c32 = l & 31, g = l >> 5;
     const int T = a.meta.T, Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
     const DeviceCsr& csr = a.meta.fwd;
     // heads of one kv group are neighbours in launch order and share an XCD when Hkv == 8
@@ -52,24 +52,28 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         dma_tile64(Kb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sKb[buf], w, l);
         dma_tile64(Vb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sVb[buf], w, l);
     };
-    int e = csr.row_ptr[qt];
-    const int e_end = csr.row_ptr[qt + 1];
+    const int e0 = csr.row_ptr[qt], n_ent = csr.row_ptr[qt + 1] - e0;
+    EntryStream es;
+    es.init(csr.entry, e0, 1, n_ent, l);
     int ent = 0, ent_next = 0, buf = 0;
-    if (e < e_end) {
-        ent = csr.entry[e];
+    if (n_ent > 0) {
+        ent = es.get(0);
         fetch(ent, 0);
-        if (e + 1 < e_end) ent_next = csr.entry[e + 1];
     }
-    for (; e < e_end; ++e, buf ^= 1) {
+    // Q fragments are in registers before the loop starts, so the loop body holds no wait
+    // on a compiler-tracked load (such a wait would also cover the copies in flight)
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    for (int it = 0; it < n_ent; ++it, buf ^= 1) {
+        // this wave's copies of tile `it` have landed; after the barrier every wave's
+        // have, and every wave has left the other buffer
+        dma_wait_barrier<0>();
+        if (it + 1 < n_ent) {
+            ent_next = es.get(it + 1);
+            fetch(ent_next, buf ^ 1);
+        }
         const int k0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
-        // this tile has landed (vmcnt) and every wave has left the other buffer
-        __syncthreads();
-        if (e + 1 < e_end) {
-            fetch(ent_next, buf ^ 1);
-            ent = ent_next;
-            if (e + 2 < e_end) ent_next = csr.entry[e + 2];
-        }
+        ent = ent_next;
         const char* sK = sKb[buf];
         const char* sV = sVb[buf];
         // 32 MFMA slots per tile: 0-15 S^T = K Q^T (rows = keys, column = this lane's
