@@ -15,6 +15,12 @@ SOURCES = ["psattn_meta.cpp", "psattn_api.hip", "psattn_generic.hip", "psattn_mf
 # otherwise forms them from ordinary float arithmetic).
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
+# The dK/dV kernel needs more than 256 registers per lane.  By default the compiler then
+# makes every MFMA write its result to the accumulation registers, which the vector ALU
+# cannot read, and the scores would cost one register move per element; with this option
+# MFMA results stay in ordinary registers and only the overflow lives in the others.
+SOURCE_FLAGS = {"psattn_mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
 
 def hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
@@ -32,7 +38,7 @@ def build(verbose: bool = True, extra=()) -> str:
     for src in SOURCES:
         obj = os.path.join(bdir, src + ".o")
         cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",
-               "-I", os.path.join(ROOT, "include"), "-I", CSRC, *DEVICE_FLAGS, *extra,
+               "-I", os.path.join(ROOT, "include"), "-I", CSRC, *DEVICE_FLAGS, *SOURCE_FLAGS.get(src, []), *extra,
                "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)

@@ -65,10 +65,11 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     // K / V tiles are copied global -> LDS asynchronously, one tile ahead, into the
     // buffer the previous tile has just vacated; one barrier per tile.
     const uint32_t row_bytes = static_cast<uint32_t>(Hkv) * 256u;
+    const DmaLane dml = dma_lane(row_bytes, w, l);
     auto fetch = [&](int ent, int buf) {
         const int k0 = (ent >> 2) * 64;
-        dma_tile64(reinterpret_cast<const char*>(K) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sKb[buf], w, l);
-        dma_tile64(reinterpret_cast<const char*>(V) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sVb[buf], w, l);
+        dma_tile64(reinterpret_cast<const char*>(K) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dml, sKb[buf], w, l);
+        dma_tile64(reinterpret_cast<const char*>(V) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dml, sVb[buf], w, l);
     };
     const int e0 = csr.row_ptr[qt], n_ent = csr.row_ptr[qt + 1] - e0;
     EntryStream es;
@@ -291,12 +292,13 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
     // last token: whatever they hold is removed by the pair masks (a clipped tile is
     // never FULL).
     const uint32_t row_bytes = static_cast<uint32_t>(Hq) * 256u;
+    const DmaLane dml = dma_lane(row_bytes, w, l);
     auto prefetch = [&](int ent, int h, int buf) {
         const int q0 = (ent >> 2) * 64;
         const size_t tile_elems = (static_cast<size_t>(q0) * Hq + h) * 128;
         const int rmax = T - 1 - q0;
-        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.Q) + tile_elems), row_bytes, rmax, sQ[buf], w, l);
-        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems), row_bytes, rmax, sG[buf], w, l);
+        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.Q) + tile_elems), row_bytes, rmax, dml, sQ[buf], w, l);
+        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems), row_bytes, rmax, dml, sG[buf], w, l);
         if (w < 2) {  // wave 0: 64 x LSE * log2 e, wave 1: 64 x delta, one dword per lane
             const float* src = (w ? a.delta : a.lse2) + static_cast<size_t>(h) * T + q0 + min(l, rmax);
             dma4(src, lds_addr(w ? sD[buf] : sL[buf]));

@@ -165,10 +165,6 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) char*)p));
 }
 
-__device__ __forceinline__ void dma16(const void* src, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(src) : "memory");
-}
-
 __device__ __forceinline__ void dma4(const void* src, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(src) : "memory");
 }
@@ -178,21 +174,44 @@ __device__ __forceinline__ void dma_wait_barrier() {
     asm volatile("s_waitcnt vmcnt(%0)\n\ts_barrier" ::"n"(N) : "memory");
 }
 
-// Copy of a 64-row tile (256-byte rows) into a swizzled LDS tile.  A wave instruction
-// fills four tile rows, so the swizzle is applied on the global side: lane l fetches the
-// logical chunk that belongs at physical chunk l % 16 of row r4 + l / 16.  Each of the
-// four waves of a workgroup copies 16 rows (4 copies per lane).  `base` points at the
-// tile's first row, rows are `row_bytes` apart; rows past `last_row` re-read that row.
-// `w` must be wave-uniform.
-__device__ __forceinline__ void dma_tile64(const char* base, uint32_t row_bytes, int last_row, const char* tile, int w, int l) {
-    const uint32_t lds = lds_addr(tile);
+// Copy of a 64-row tile (256-byte rows, rows `row_bytes` apart in global memory) into a
+// swizzled LDS tile.  A wave instruction fills four tile rows, so the swizzle is applied
+// on the global side: lane l fetches the logical chunk that belongs at physical chunk
+// l % 16 of row r4 + l / 16.  Each of the four waves of a workgroup copies 16 rows in 4
+// instructions; DmaLane holds the lane's byte offsets for them, so that a copy costs no
+// vector ALU work: the address is a scalar tile base plus that 32-bit lane offset.
+struct DmaLane {
+    uint32_t off[4];
+};
+
+// `w` (wave index in the workgroup) must be wave-uniform; rows past `last_row` re-read it
+__device__ __forceinline__ DmaLane dma_lane(uint32_t row_bytes, int w, int l, int last_row = 63) {
+    DmaLane d;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int r4 = 16 * w + 4 * i;
-        const int row = r4 + (l >> 4);
+        const int row = 16 * w + 4 * i + (l >> 4);
         const int sw = ((row & 3) << 2) | ((row >> 2) & 3);
-        const char* src = base + static_cast<uint32_t>(min(row, last_row)) * row_bytes + (((l & 15) ^ sw) << 4);
-        dma16(src, lds + r4 * kRowBytes);
+        d.off[i] = static_cast<uint32_t>(min(row, last_row)) * row_bytes + (((l & 15) ^ sw) << 4);
+    }
+    return d;
+}
+
+__device__ __forceinline__ void dma16(const void* base, uint32_t lane_off, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(lane_off), "s"(base) : "memory");
+}
+
+// `base`: first row of the tile (wave-uniform); `tile`: LDS tile; `full`: the lane offsets
+// of an unclipped tile; a tile whose last valid row is < 63 takes the clamped offsets.
+__device__ __forceinline__ void dma_tile64(const char* base, uint32_t row_bytes, int last_row, const DmaLane& full, const char* tile, int w, int l) {
+    const uint32_t lds = lds_addr(tile) + 16 * w * kRowBytes;
+    if (last_row >= 63) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16(base, full.off[i], lds + 4 * i * kRowBytes);
+    } else {
+        asm volatile("; clipped tile" : "+s"(last_row));  // keeps the clamped offsets' arithmetic in this branch
+        const DmaLane c = dma_lane(row_bytes, w, l, last_row);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) dma16(base, c.off[i], lds + 4 * i * kRowBytes);
     }
 }
 

@@ -41,39 +41,42 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
     const float c = a.scale * kLog2e;
     const LaneOffsets lo = lane_offsets(l);
     constexpr int kAhead = 3, kRing = 4;
+    constexpr float kSlack = 0.f;
 
     // K / V tiles are copied global -> LDS asynchronously, one tile ahead, into the
     // buffer the previous tile has just vacated; one barrier per tile.
     const uint32_t row_bytes = static_cast<uint32_t>(Hkv) * 256u;
     const char* Kb = reinterpret_cast<const char*>(K);
     const char* Vb = reinterpret_cast<const char*>(V);
-    auto fetch = [&](int ent, int buf) {
+    const DmaLane dl = dma_lane(row_bytes, w, l);
+    auto fetch = [&](int ent, auto BUF) {
+        constexpr int buf = decltype(BUF)::value;
         const int k0 = (ent >> 2) * 64;
-        dma_tile64(Kb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sKb[buf], w, l);
-        dma_tile64(Vb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, sVb[buf], w, l);
+        dma_tile64(Kb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dl, sKb[buf], w, l);
+        dma_tile64(Vb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dl, sVb[buf], w, l);
     };
     const int e0 = csr.row_ptr[qt], n_ent = csr.row_ptr[qt + 1] - e0;
     EntryStream es;
     es.init(csr.entry, e0, 1, n_ent, l);
-    int ent = 0, ent_next = 0, buf = 0;
+    int ent = 0, it = 0;
     if (n_ent > 0) {
         ent = es.get(0);
-        fetch(ent, 0);
+        fetch(ent, std::integral_constant<int, 0>{});
     }
-    // Q fragments are in registers before the loop starts, so the loop body holds no wait
-    // on a compiler-tracked load (such a wait would also cover the copies in flight)
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    for (int it = 0; it < n_ent; ++it, buf ^= 1) {
+    // One tile.  The buffer index is a compile-time constant (the loop below is unrolled
+    // by two), so every LDS address is a lane constant plus an immediate offset.
+    auto tile = [&](auto BUF) {
+        constexpr int buf = decltype(BUF)::value;
         // this wave's copies of tile `it` have landed; after the barrier every wave's
         // have, and every wave has left the other buffer
         dma_wait_barrier<0>();
-        if (it + 1 < n_ent) {
-            ent_next = es.get(it + 1);
-            fetch(ent_next, buf ^ 1);
-        }
         const int k0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
-        ent = ent_next;
+        if (it + 1 < n_ent) {
+            ent = es.get(it + 1);
+            fetch(ent, std::integral_constant<int, buf ^ 1>{});
+        }
+        ++it;
         const char* sK = sKb[buf];
         const char* sV = sVb[buf];
         // 32 MFMA slots per tile: 0-15 S^T = K Q^T (rows = keys, column = this lane's
@@ -103,6 +106,7 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
             __builtin_amdgcn_sched_barrier(0);
         });
         if (!full) {
+            asm volatile("; mask of a PARTIAL tile" ::: "memory");
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
@@ -118,11 +122,14 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
         mx = fmaxf(mx, other_half(mx));
+        // The reference maximum m only has to keep exp2 in range, not to be the exact
+        // running maximum: it moves only when the new maximum exceeds it by more than
+        // kSlack (in base-2 exponent units), so p <= 2^kSlack and rescaling is rare.
         const float m_new = fmaxf(m, mx * c);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        // the running maximum rarely moves once a row has seen many keys: rescale only then
-        if (__builtin_amdgcn_ballot_w64(m_new != m) != 0) {
-            const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+        if (__builtin_amdgcn_ballot_w64(m_new > m + kSlack) != 0) {
+            asm volatile("; rescale" ::: "memory");
+            const float m_to = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m - m_to);  // m = -inf: 0 (nothing accumulated yet)
             lsum *= alpha;
 #pragma unroll
             for (int db = 0; db < 4; ++db)
@@ -130,6 +137,7 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
                 for (int i = 0; i < 16; ++i) o[db][i] *= alpha;
             m = m_new;
         }
+        const float m_use = m == -INFINITY ? 0.f : m;
         float psum = 0.f;
         bf16x8 pb[2][2];
 #pragma unroll
@@ -145,12 +153,20 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         lsum += psum;
         __builtin_amdgcn_sched_barrier(0);
         static_for<16, 32>([&](auto M) {
-            constexpr int m = decltype(M)::value, j = m - 16, kb = j >> 3, half = (j >> 2) & 1, db = j & 3;
-            request(std::integral_constant<int, m + kAhead>{});
-            o[db] = mfma(ring[m % kRing].v, pb[kb][half], o[db]);
+            constexpr int m_ = decltype(M)::value, j = m_ - 16, kb = j >> 3, half = (j >> 2) & 1, db = j & 3;
+            request(std::integral_constant<int, m_ + kAhead>{});
+            o[db] = mfma(ring[m_ % kRing].v, pb[kb][half], o[db]);
             __builtin_amdgcn_sched_barrier(0);
         });
+    };
+    // Q fragments are in registers before the loop starts, so the loop body holds no wait
+    // on a compiler-tracked load (such a wait would also cover the copies in flight)
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    while (it + 1 < n_ent) {
+        tile(std::integral_constant<int, 0>{});
+        tile(std::integral_constant<int, 1>{});
     }
+    if (it < n_ent) tile(std::integral_constant<int, 0>{});
     const float l_tot = lsum + other_half(lsum);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (valid) {
