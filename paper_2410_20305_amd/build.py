@@ -9,18 +9,16 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsattn.so")
-SOURCES = ["psattn_meta.cpp", "psattn_api.hip", "psattn_generic.hip", "psattn_mfma_fwd.hip", "psattn_mfma_bwd.hip"]
+SOURCES = ["psattn_meta.cpp", "psattn_api.hip", "psattn_generic.hip", "psattn_mfma_fwd.hip", "psattn_mfma_bwd.hip",
+           "psattn_mfma_dkdv.hip"]
 
 # Packed-fp32 VALU instructions are switched off for all device code (the compiler
 # otherwise forms them from ordinary float arithmetic).
 DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
-# The dK/dV kernel needs more than 256 registers per lane.  By default the compiler then
-# makes every MFMA write its result to the accumulation registers, which the vector ALU
-# cannot read, and the scores would cost one register move per element; with this option
-# MFMA results stay in ordinary registers and only the overflow lives in the others.
-SOURCE_FLAGS = {"psattn_mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
-
+# The dK/dV kernel manages the accumulation registers a[0:191] itself (see the head of its
+# source file); the compiler must not park spilled values there.
+SOURCE_FLAGS = {"psattn_mfma_dkdv.hip": ["-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"]}
 
 def hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):

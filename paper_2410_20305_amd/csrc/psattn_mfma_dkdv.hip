@@ -1,0 +1,301 @@
+// bf16 MFMA dK/dV kernel for gfx950; layout and staging helpers are in psattn_mfma_common.h.
+//
+// grid: one workgroup per (k-tile of 128 keys, kv-head); 4 waves x 32 keys, one wave per
+// SIMD.  The workgroup walks the G query heads of its group and, for each, the q-tiles
+// (64 queries) that can read its keys (the k-major tile list of the block mask, paper
+// Section 3.1), so the prompt's keys collect the contributions of prompt, chosen and
+// rejected queries in one place, without atomics.
+//
+// Register plan.  A wave keeps dK and dV of its 32 keys (2 x 64 fp32 per lane) and its K
+// and V fragments (2 x 32 registers per lane) for the whole kernel: 192 registers that only
+// MFMA instructions ever touch.  They live in the accumulation registers a[0:191], which
+// MFMA reads and writes directly and the vector ALU cannot address; the ordinary registers
+// are left to the scores, the LDS operand ring and the softmax arithmetic.  The compiler
+// cannot express this split (once a kernel needs more than 256 registers it sends either
+// every MFMA result or none to the accumulation registers, and moves whole accumulators
+// back and forth), so all MFMAs of this kernel are issued from inline assembly that names
+// the accumulation registers itself; everything else is ordinary compiled code.  This file
+// is built with the compiler's own use of accumulation registers for spilling switched off,
+// so a[0:191] belong to the assembly alone.
+//
+// The compiler does not know that the assembly statements are MFMAs and inserts no wait
+// states after them: settle() stands wherever another kind of instruction reads what a
+// chain of MFMAs has produced.
+#include "psattn_mfma_common.h"
+
+namespace psattn {
+namespace {
+using namespace mma;
+
+constexpr int kAccDV = 0;     // a[16 db + i]: dV^T block db (head dims 32 db ..), accumulator element i
+constexpr int kAccDK = 64;    // likewise dK^T
+constexpr int kRegK = 128;    // a[128 + 4 t ..]: K fragment of step t (head dims 16 t ..), B operand
+constexpr int kRegV = 160;    // likewise V
+constexpr int kAccRegs = 192;
+
+// a[A0 : A0 + 15] += x y
+template <int A0>
+__device__ __forceinline__ void acc_mfma(bf16x8 x, bf16x8 y) {
+    asm volatile("v_mfma_f32_32x32x16_bf16 a[%0:%1], %2, %3, a[%0:%1]" ::"n"(A0), "n"(A0 + 15), "v"(x), "v"(y));
+}
+
+// acc (ordinary registers) = x * a[B0 : B0 + 3] (+ acc unless FIRST)
+template <int B0, bool FIRST>
+__device__ __forceinline__ void score_mfma(f32x16& acc, bf16x8 x) {
+    if constexpr (FIRST)
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[%2:%3], 0" : "=&v"(acc) : "v"(x), "n"(B0), "n"(B0 + 3));
+    else
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, a[%2:%3], %0" : "+v"(acc) : "v"(x), "n"(B0), "n"(B0 + 3));
+}
+
+template <int A>
+__device__ __forceinline__ void acc_set(uint32_t v) {
+    asm volatile("v_accvgpr_write_b32 a[%0], %1" ::"n"(A), "v"(v));
+}
+
+template <int A>
+__device__ __forceinline__ float acc_get() {
+    float v;
+    asm volatile("v_accvgpr_read_b32 %0, a[%1]" : "=v"(v) : "n"(A));
+    return v;
+}
+
+// 24 wait states: more than the longest MFMA needs before its result may be read
+__device__ __forceinline__ void settle() {
+    asm volatile("s_nop 15\n\ts_nop 7" ::: "memory");
+}
+
+// ------------------------------------------------------------------ one q-tile
+// With one wave per SIMD nothing hides latency but the wave's own instruction stream, so a
+// q-tile is processed as 64 explicitly ordered slots, one MFMA each:
+//   slots  0-15  S, dP of queries 0-31
+//   slots 16-31  S, dP of queries 32-63      + softmax/dS arithmetic of queries 0-31
+//   slots 32-47  dV, dK from queries 0-31    + softmax/dS arithmetic of queries 32-63
+//   slots 48-63  dV, dK from queries 32-63
+// The LDS operand of slot m is requested kAhead slots earlier into a register ring.
+
+constexpr int kQTileBytes = 64 * kRowBytes;
+constexpr int kAhead = 5;
+
+// Number of accumulator elements e = 16 b + i (b = 32-query block, i = register) of
+// lane-half g whose tile row 32 b + acc_row(i, g) lies below x, 0 <= x <= 64.
+__device__ inline int elems_below(int x, int g) {
+    return 4 * (x >> 3) + min(max((x & 7) - 4 * g, 0), 4);
+}
+
+// AND-masks for the packed bf16 pairs (elements 2j, 2j + 1 of block b) of one q-tile:
+// the queries allowed to read this lane's key are rows [lo, hi) of the tile.
+__device__ inline void pair_masks(uint32_t (&mw)[2][8], int lo, int hi, int g) {
+    const int a = elems_below(min(max(lo, 0), 64), g), b = elems_below(min(max(hi, 0), 64), g);
+    const uint32_t bits = static_cast<uint32_t>(((1ull << b) - 1) & ~((1ull << a) - 1));
+#pragma unroll
+    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int e = 16 * b2 + 2 * j;
+            mw[b2][j] = ((bits >> e) & 1u ? 0x0000ffffu : 0u) | ((bits >> (e + 1)) & 1u ? 0xffff0000u : 0u);
+        }
+}
+
+__device__ inline uint32_t pack2(float a, float b) {
+    f32x2 v = {a, b};
+    union { bf16x2 p; uint32_t u; } o;
+    o.p = __builtin_convertvector(v, bf16x2);
+    return o.u;
+}
+
+__device__ inline float comp(const float4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
+
+// FULL: every pair of the tile is allowed, no mask work at all (mw is not read)
+template <bool FULL>
+__device__ __forceinline__ void dkdv_tile(const char* sQ, const char* sG, const float* sL, const float* sD,
+                                          const LaneOffsets& lo, const uint32_t (&mw)[2][8], float c, int g) {
+    Frag8 ring[8];
+    f32x16 s[2], dp[2];
+    u32x4 pw[2][2], dw[2][2];  // packed P and dS of a block: [block][half] is one B operand
+    float4 Lc, Dc, Ln, Dn;
+    float p0 = 0.f, p1 = 0.f;
+
+    auto request = [&](auto M) {  // LDS operand of slot m -> ring[m % 8]
+        constexpr int m = decltype(M)::value;
+        if constexpr (m < 32) {
+            constexpr int b = m >> 4, t = (m & 15) >> 1;
+            const char* x = (m & 1) ? sG : sQ;
+            ring[m & 7].v = ld_rows<t>(x + b * 32 * kRowBytes, lo.nat);
+        } else if constexpr (m < 64) {
+            constexpr int j = (m - 32) & 15, b = (m - 32) >> 4, half = j >> 3, db = (j & 7) >> 1;
+            const char* x = (j & 1) ? sQ : sG;
+            ring[m & 7].v = ld_cols<db, half>(x + 32 * b * kRowBytes, lo.tr1, lo.tr2);
+        }
+    };
+    auto stats = [&](int b, int i4, float4& L, float4& D) {  // LSE, delta of 4 consecutive queries
+        const int r = 32 * b + 8 * i4 + 4 * g;
+        L = *reinterpret_cast<const float4*>(sL + r);
+        D = *reinterpret_cast<const float4*>(sD + r);
+    };
+
+    static_for<0, kAhead>([&](auto M) { request(M); });
+    stats(0, 0, Lc, Dc);
+    static_for<0, 64>([&](auto M) {
+        constexpr int m = decltype(M)::value;
+        request(std::integral_constant<int, m + kAhead>{});
+        if constexpr (m < 32) {
+            constexpr int b = m >> 4, t = (m & 15) >> 1;
+            if constexpr (m & 1) score_mfma<kRegV + 4 * t, t == 0>(dp[b], ring[m & 7].v);  // dP = dO V^T
+            else score_mfma<kRegK + 4 * t, t == 0>(s[b], ring[m & 7].v);                     // S  = Q K^T
+        } else {
+            constexpr int j = (m - 32) & 15, b = (m - 32) >> 4, half = j >> 3, db = (j & 7) >> 1;
+            if constexpr (j & 1) acc_mfma<kAccDK + 16 * db>(ring[m & 7].v, __builtin_bit_cast(bf16x8, dw[b][half]));
+            else acc_mfma<kAccDV + 16 * db>(ring[m & 7].v, __builtin_bit_cast(bf16x8, pw[b][half]));
+        }
+        if constexpr (m >= 16 && m < 48) {
+            // slot pair (2j, 2j + 1) of the phase turns accumulator elements 2j, 2j + 1 of
+            // block b into packed P (even slot) and packed dS (odd slot)
+            constexpr int n = m - 16, b = n >> 4, k = n & 15, j = k >> 1, i = 2 * j;
+            // S of block b was finished two MFMAs ago when k = 0, dP when k = 1
+            if constexpr (k < 2) settle();
+            if constexpr ((k & 3) == 0 && n + 4 < 32) stats((n + 4) >> 4, ((n + 4) & 15) >> 2, Ln, Dn);
+            if constexpr ((k & 1) == 0) {
+                p0 = __builtin_amdgcn_exp2f(fmaf(s[b][i], c, -comp(Lc, i & 3)));
+                p1 = __builtin_amdgcn_exp2f(fmaf(s[b][i + 1], c, -comp(Lc, (i + 1) & 3)));
+                pw[b][j >> 2][j & 3] = FULL ? pack2(p0, p1) : pack2(p0, p1) & mw[b][j];
+            } else {
+                const float d0 = p0 * (dp[b][i] - comp(Dc, i & 3));
+                const float d1 = p1 * (dp[b][i + 1] - comp(Dc, (i + 1) & 3));
+                dw[b][j >> 2][j & 3] = FULL ? pack2(d0, d1) : pack2(d0, d1) & mw[b][j];
+            }
+            if constexpr ((k & 3) == 3) { Lc = Ln; Dc = Dn; }
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    });
+}
+
+__global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
+    __shared__ __attribute__((aligned(16))) char sQ[2][kQTileBytes];
+    __shared__ __attribute__((aligned(16))) char sG[2][kQTileBytes];  // dO
+    __shared__ __attribute__((aligned(16))) float sL[2][64];          // LSE * log2(e)
+    __shared__ __attribute__((aligned(16))) float sD[2][64];          // delta
+    // a[0:191] are in use: makes the kernel's register allocation cover them
+    asm volatile("" ::: "a0", "a191");
+    const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, c32 = l & 31, g = l >> 5;
+    const int T = a.meta.T, Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
+    const DeviceCsr& csr = a.meta.bwd;
+    const int kvh = blockIdx.x % Hkv, kt = csr.order[blockIdx.x / Hkv];
+    const int key = kt * 128 + 32 * w + c32;
+    const bool kvalid = key < T;
+    const int key_hi = kvalid ? a.meta.tok[key].key_hi : 0;  // queries [key, key_hi) read this key
+    const size_t koff = (static_cast<size_t>(key) * Hkv + kvh) * 128;
+
+    // K, V fragments of this lane's key -> a[128:191]; dK, dV accumulators a[0:127] = 0
+    static_for<0, 8>([&](auto TT) {
+        constexpr int t = decltype(TT)::value;
+        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+        if (kvalid) {
+            kv = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.K) + koff + 16 * t + 8 * g);
+            vv = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.V) + koff + 16 * t + 8 * g);
+        }
+        acc_set<kRegK + 4 * t + 0>(kv.x);
+        acc_set<kRegK + 4 * t + 1>(kv.y);
+        acc_set<kRegK + 4 * t + 2>(kv.z);
+        acc_set<kRegK + 4 * t + 3>(kv.w);
+        acc_set<kRegV + 4 * t + 0>(vv.x);
+        acc_set<kRegV + 4 * t + 1>(vv.y);
+        acc_set<kRegV + 4 * t + 2>(vv.z);
+        acc_set<kRegV + 4 * t + 3>(vv.w);
+    });
+    static_for<0, 128>([&](auto R) { acc_set<decltype(R)::value>(0u); });
+
+    const float c = a.scale * kLog2e;
+    const LaneOffsets lo = lane_offsets(l);
+    const int e0 = csr.row_ptr[kt], n_ent = csr.row_ptr[kt + 1] - e0;
+    const int n_it = n_ent * G;
+
+    // Staging of one q-tile (64 rows x 256 B of Q and of dO, 64 LSE * log2 e, 64 delta):
+    // asynchronous global -> LDS copies, issued one tile ahead into the buffer the
+    // previous tile has just vacated.  Rows past the end of the buffer re-read the
+    // last token: whatever they hold is removed by the pair masks (a clipped tile is
+    // never FULL).
+    const uint32_t row_bytes = static_cast<uint32_t>(Hq) * 256u;
+    const DmaLane dml = dma_lane(row_bytes, w, l);
+    auto prefetch = [&](int ent, int h, auto BUF) {
+        constexpr int buf = decltype(BUF)::value;
+        const int q0 = (ent >> 2) * 64;
+        const size_t tile_elems = (static_cast<size_t>(q0) * Hq + h) * 128;
+        const int rmax = T - 1 - q0;
+        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.Q) + tile_elems), row_bytes, rmax, dml, sQ[buf], w, l);
+        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems), row_bytes, rmax, dml, sG[buf], w, l);
+        if (w < 2) {  // wave 0: 64 x LSE * log2 e, wave 1: 64 x delta, one dword per lane
+            const float* src = (w ? a.delta : a.lse2) + static_cast<size_t>(h) * T + q0 + min(l, rmax);
+            dma4(src, lds_addr(w ? sD[buf] : sL[buf]));
+        }
+    };
+    // Walk order: q-tiles from the last to the first, and for each q-tile the G heads
+    // of the group.  Every k-tile of a sample ends at the same q-tile, so workgroups
+    // of neighbouring k-tiles (which run at the same time on the same XCD) read the
+    // same Q / dO tile at the same moment and share it through L2.
+    EntryStream es;
+    es.init(csr.entry, e0 + n_ent - 1, -1, n_ent, l);
+    int pk = 0, ph = 0;  // walk position and head (within the group) of the next tile
+    int ent = 0, it = 0;
+    if (n_it > 0) {
+        ent = es.get(0);
+        prefetch(ent, kvh * G, std::integral_constant<int, 0>{});
+        if (++ph == G) { ph = 0; ++pk; }
+    }
+    // One tile; the buffer index is a compile-time constant, so every LDS address is a lane
+    // constant plus an immediate offset.
+    auto tile = [&](auto BUF) {
+        constexpr int buf = decltype(BUF)::value;
+        // this wave's copies of tile `it` have landed; after the barrier every wave's
+        // have, and tile it - 1 (same buffer as it + 1) is no longer read
+        dma_wait_barrier<0>();
+        const int q0 = (ent >> 2) * 64;
+        const bool full = (ent & 3) == PSATTN_TILE_FULL;
+        if (it + 1 < n_it) {
+            ent = es.get(pk);
+            prefetch(ent, kvh * G + ph, std::integral_constant<int, buf ^ 1>{});
+            if (++ph == G) { ph = 0; ++pk; }
+        }
+        ++it;
+        uint32_t mw[2][8];
+        if (full) {
+            dkdv_tile<true>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g);
+        } else {
+            pair_masks(mw, key - q0, key_hi - q0, g);
+            dkdv_tile<false>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g);
+        }
+    };
+    // The K / V loads above have retired before the loop starts, so the loop body holds no
+    // wait on a compiler-tracked load (such a wait would also cover the copies in flight).
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    settle();  // the register writes above, before the first MFMA reads them
+    while (it < n_it) {
+        if (it & 1) tile(std::integral_constant<int, 1>{});
+        else tile(std::integral_constant<int, 0>{});
+    }
+    settle();  // the last MFMAs, before dK / dV are read out
+    if (kvalid) {
+        uint16_t* krow = static_cast<uint16_t*>(a.dK) + koff;
+        uint16_t* vrow = static_cast<uint16_t*>(a.dV) + koff;
+        const float sc = a.scale;
+        static_for<0, 16>([&](auto Q4) {
+            constexpr int q4 = decltype(Q4)::value, db = q4 >> 2, i4 = q4 & 3;
+            const int d = 32 * db + 8 * i4 + 4 * g;
+            store4(krow + d, acc_get<kAccDK + 16 * db + 4 * i4 + 0>() * sc, acc_get<kAccDK + 16 * db + 4 * i4 + 1>() * sc,
+                   acc_get<kAccDK + 16 * db + 4 * i4 + 2>() * sc, acc_get<kAccDK + 16 * db + 4 * i4 + 3>() * sc);
+            store4(vrow + d, acc_get<kAccDV + 16 * db + 4 * i4 + 0>(), acc_get<kAccDV + 16 * db + 4 * i4 + 1>(),
+                   acc_get<kAccDV + 16 * db + 4 * i4 + 2>(), acc_get<kAccDV + 16 * db + 4 * i4 + 3>());
+        });
+    }
+}
+
+}  // namespace
+
+int launch_mfma_dkdv(const AttnArgs& a, void* stream) {
+    const unsigned grid = static_cast<unsigned>(a.meta.bwd.n_rows) * a.Hkv;
+    if (grid == 0) return 0;
+    psattn_dkdv_bf16_mfma<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(a);
+    return static_cast<int>(hipGetLastError());
+}
+
+}  // namespace psattn
