@@ -31,8 +31,10 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
         gf[t].u = valid ? *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(a.dO) + qoff + 16 * t + 8 * g)
                         : make_uint4(0, 0, 0, 0);
     }
-    // rows without keys (padding) keep LSE = -inf; every pair of theirs is masked below
-    const float lse2 = valid ? a.LSE[static_cast<size_t>(h) * T + q_row] * kLog2e : INFINITY;
+    // Rows without keys (padding) have LSE = -inf.  Their scores are masked to -inf below;
+    // with +inf here exp2(score - lse2) is 0 for them instead of exp2(-inf + inf).
+    const float lse_row = valid ? a.LSE[static_cast<size_t>(h) * T + q_row] : -INFINITY;
+    const float lse2 = lse_row == -INFINITY ? INFINITY : lse_row * kLog2e;
     // delta = rowsum(dO o O): this lane holds half of the row's dO already, O is read once
     // here; the result also goes to the workspace for the dK/dV pass that follows
     float dl = 0.f;
@@ -66,7 +68,8 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     // buffer the previous tile has just vacated; one barrier per tile.
     const uint32_t row_bytes = static_cast<uint32_t>(Hkv) * 256u;
     const DmaLane dml = dma_lane(row_bytes, w, l);
-    auto fetch = [&](int ent, int buf) {
+    auto fetch = [&](int ent, auto BUF) {
+        constexpr int buf = decltype(BUF)::value;
         const int k0 = (ent >> 2) * 64;
         dma_tile64(reinterpret_cast<const char*>(K) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dml, sKb[buf], w, l);
         dma_tile64(reinterpret_cast<const char*>(V) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dml, sVb[buf], w, l);
@@ -74,57 +77,104 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     const int e0 = csr.row_ptr[qt], n_ent = csr.row_ptr[qt + 1] - e0;
     EntryStream es;
     es.init(csr.entry, e0, 1, n_ent, l);
-    int ent = 0, ent_next = 0, buf = 0;
+    int ent = 0, it = 0;
     if (n_ent > 0) {
         ent = es.get(0);
-        fetch(ent, 0);
+        fetch(ent, std::integral_constant<int, 0>{});
     }
-    // every compiler-tracked load and store above has retired before the loop starts, so
-    // the loop body holds no wait of the compiler's that would also cover copies in flight
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
-    for (int it = 0; it < n_ent; ++it, buf ^= 1) {
-        // this wave's copies of tile `it` have landed; after the barrier every wave's
-        // have, and every wave has left the other buffer
-        dma_wait_barrier<0>();
-        if (it + 1 < n_ent) {
-            ent_next = es.get(it + 1);
-            fetch(ent_next, buf ^ 1);
-        }
-        const int k0 = (ent >> 2) * 64;
-        const bool full = (ent & 3) == PSATTN_TILE_FULL;
-        ent = ent_next;
+    const LaneOffsets lo = lane_offsets(l);
+    constexpr int kAhead = 3, kRing = 4;
+    // One tile = 48 MFMA slots, per block kb of 32 keys:
+    //   slots 24 kb +  0-15  S^T = K Q^T and dP^T = V dO^T (alternating)
+    //   (dS arithmetic of the block)
+    //   slots 24 kb + 16-23  dQ^T += K^T dS^T
+    // The LDS operand of slot m is requested kAhead slots earlier into a register ring,
+    // across the arithmetic too.  Two workgroups share a CU: the other wave of the SIMD
+    // fills the gaps.  The buffer index is a compile-time constant (the loop below is
+    // unrolled by two), so every LDS address is a lane constant plus an immediate offset.
+    // Only PARTIAL tiles (full == false) run the mask arithmetic.
+    auto tile = [&](auto BUF, int k0, bool full) {
+        constexpr int buf = decltype(BUF)::value;
         const char* sK = sKb[buf];
         const char* sV = sVb[buf];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        Frag8 ring[kRing];
+        auto request = [&](auto M) {
+            constexpr int m = decltype(M)::value;
+            if constexpr (m < 48) {
+                constexpr int kb = m / 24, j = m % 24;
+                if constexpr (j < 16) {
+                    constexpr int t = j >> 1;
+                    ring[m % kRing].v = ld_rows<t>(((j & 1) ? sV : sK) + kb * 32 * kRowBytes, lo.nat);
+                } else {
+                    constexpr int half = (j >> 2) & 1, db = j & 3;
+                    ring[m % kRing].v = ld_cols<db, half>(sK + 32 * kb * kRowBytes, lo.tr1, lo.tr2);
+                }
+            }
+        };
+        static_for<0, kAhead>([&](auto M) { request(M); });
+        static_for<0, 2>([&](auto KB) {
+            constexpr int kb = decltype(KB)::value;
             f32x16 s, dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }
+            static_for<0, 16>([&](auto J) {
+                constexpr int j = decltype(J)::value, m = 24 * kb + j, t = j >> 1;
+                request(std::integral_constant<int, m + kAhead>{});
+                if constexpr (j & 1) dp = mfma(ring[m % kRing].v, gf[t].v, dp);
+                else s = mfma(ring[m % kRing].v, qf[t].v, s);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            if (!full) {
+                // key index of accumulator element i: jb + 8 (i / 4) + i % 4; the statement below
+                // keeps the sixteen sums from being kept in registers across the whole loop
+                int jb = k0 + 32 * kb + 4 * g;
+                asm volatile("; mask of a PARTIAL tile" : "+v"(jb));
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
-                s = mfma(lds_rows(sK, 32 * kb + c32, 2 * t + g), qf[t].v, s);    // S^T  = K Q^T
-                dp = mfma(lds_rows(sV, 32 * kb + c32, 2 * t + g), gf[t].v, dp);  // dP^T = V dO^T
+                for (int i = 0; i < 16; ++i) {
+                    const int j = jb + 8 * (i >> 2) + (i & 3);
+                    const bool ok = (j >= tk.s) & (j <= q_row) & !((j >= tk.hole_lo) & (j < tk.hole_hi));
+                    s[i] = ok ? s[i] : -INFINITY;  // p = 0 below
+                }
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                float p = __builtin_amdgcn_exp2f(fmaf(s[i], c, -lse2));
-                if (!full) {
-                    const int j = k0 + 32 * kb + acc_row(i, g);
-                    const bool ok = j >= tk.s && j <= q_row && !(j >= tk.hole_lo && j < tk.hole_hi);
-                    p = ok ? p : 0.f;
-                }
+                const float p = __builtin_amdgcn_exp2f(fmaf(s[i], c, -lse2));
                 s[i] = p * (dp[i] - dl);  // dS^T
             }
-            // dQ^T += K^T dS^T
-#pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                const bf16x8 dsb = pack8(s, half);
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-                    dq[db] = mfma(lds_cols(sK, 32 * kb + 16 * half, 32 * db, l), dsb, dq[db]);
-            }
+            bf16x8 dsb[2];
+            dsb[0] = pack8(s, 0);
+            dsb[1] = pack8(s, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            static_for<16, 24>([&](auto J) {
+                constexpr int j = decltype(J)::value, m = 24 * kb + j, half = (j >> 2) & 1, db = j & 3;
+                request(std::integral_constant<int, m + kAhead>{});
+                dq[db] = mfma(ring[m % kRing].v, dsb[half], dq[db]);
+                __builtin_amdgcn_sched_barrier(0);
+            });
+        });
+    };
+    auto step = [&](auto BUF) {
+        constexpr int buf = decltype(BUF)::value;
+        // this wave's copies of tile `it` have landed; after the barrier every wave's
+        // have, and every wave has left the other buffer
+        dma_wait_barrier<0>();
+        const int k0 = (ent >> 2) * 64;
+        const bool full = (ent & 3) == PSATTN_TILE_FULL;
+        if (it + 1 < n_ent) {
+            ent = es.get(it + 1);
+            fetch(ent, std::integral_constant<int, buf ^ 1>{});
         }
+        ++it;
+        tile(BUF, k0, full);
+    };
+    // every compiler-tracked load and store above has retired before the loop starts, so
+    // the loop body holds no wait of the compiler's that would also cover copies in flight
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    while (it + 1 < n_ent) {
+        step(std::integral_constant<int, 0>{});
+        step(std::integral_constant<int, 1>{});
     }
+    if (it < n_ent) step(std::integral_constant<int, 0>{});
     if (valid) {
         uint16_t* row = static_cast<uint16_t*>(a.dQ) + qoff;
         const float sc = a.scale;

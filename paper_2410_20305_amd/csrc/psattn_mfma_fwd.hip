@@ -112,7 +112,7 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int j = k0 + 32 * kb + acc_row(i, g);
-                    const bool ok = j >= tk.s && j <= q_row && !(j >= tk.hole_lo && j < tk.hole_hi);
+                    const bool ok = (j >= tk.s) & (j <= q_row) & !((j >= tk.hole_lo) & (j < tk.hole_hi));
                     s[kb][i] = ok ? s[kb][i] : -INFINITY;
                 }
         }
