@@ -81,7 +81,7 @@ struct AttnArgs {
     const float* LSE;
     void *Oout, *dQ, *dK, *dV;
     float* LSEout;
-    float* delta;  // [Hq, T]  workspace: rowsum(dO o O)
+    float* delta;  // [Hq, T]  workspace: rowsum(dO o O); the MFMA kernels keep its negative here
     float* lse2;   // [Hq, T]  workspace: LSE * log2(e), written by the MFMA dQ pass for the dK/dV pass
 };
 

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     }
     dl += other_half(dl);
     if (valid && g == 0) {
-        a.delta[static_cast<size_t>(h) * T + q_row] = dl;
+        a.delta[static_cast<size_t>(h) * T + q_row] = -dl;  // the dK/dV kernel starts its dP accumulators from -delta
         a.lse2[static_cast<size_t>(h) * T + q_row] = lse2;
     }
     const float c = a.scale * kLog2e;

@@ -106,14 +106,17 @@ __device__ inline uint32_t pack2(float a, float b) {
 
 __device__ inline float comp(const float4& v, int i) { return i == 0 ? v.x : i == 1 ? v.y : i == 2 ? v.z : v.w; }
 
-// FULL: every pair of the tile is allowed, no mask work at all (mw is not read)
-template <bool FULL>
+// FULL: every pair of the tile is allowed, no mask work at all (mw is not read).
+// copy_piece(k), k = 0 .. 8, issues one instruction of the next tile's asynchronous copy;
+// the pieces are spread over the first slots, whose only other work is MFMAs.
+template <bool FULL, typename CopyPiece>
 __device__ __forceinline__ void dkdv_tile(const char* sQ, const char* sG, const float* sL, const float* sD,
-                                          const LaneOffsets& lo, const uint32_t (&mw)[2][8], float c, int g) {
+                                          const LaneOffsets& lo, const uint32_t (&mw)[2][8], float c, int g,
+                                          CopyPiece&& copy_piece) {
     Frag8 ring[8];
     f32x16 s[2], dp[2];
     u32x4 pw[2][2], dw[2][2];  // packed P and dS of a block: [block][half] is one B operand
-    float4 Lc, Dc, Ln, Dn;
+    float4 Lc, Ln;
     float p0 = 0.f, p1 = 0.f;
 
     auto request = [&](auto M) {  // LDS operand of slot m -> ring[m % 8]
@@ -128,21 +131,32 @@ __device__ __forceinline__ void dkdv_tile(const char* sQ, const char* sG, const 
             ring[m & 7].v = ld_cols<db, half>(x + 32 * b * kRowBytes, lo.tr1, lo.tr2);
         }
     };
-    auto stats = [&](int b, int i4, float4& L, float4& D) {  // LSE, delta of 4 consecutive queries
-        const int r = 32 * b + 8 * i4 + 4 * g;
-        L = *reinterpret_cast<const float4*>(sL + r);
-        D = *reinterpret_cast<const float4*>(sD + r);
+    // dP accumulators of block b start from -delta of their queries (element i belongs to
+    // query 32 b + acc_row(i, g)), so that dS = P o (dP - delta) is one multiplication
+    auto start_dp = [&](auto B) {
+        constexpr int b = decltype(B)::value;
+#pragma unroll
+        for (int i4 = 0; i4 < 4; ++i4) {
+            const float4 d = *reinterpret_cast<const float4*>(sD + 32 * b + 8 * i4 + 4 * g);
+            dp[b][4 * i4] = d.x; dp[b][4 * i4 + 1] = d.y; dp[b][4 * i4 + 2] = d.z; dp[b][4 * i4 + 3] = d.w;
+        }
+    };
+    auto lse4 = [&](int b, int i4) {  // LSE * log2 e of 4 consecutive queries
+        return *reinterpret_cast<const float4*>(sL + 32 * b + 8 * i4 + 4 * g);
     };
 
     static_for<0, kAhead>([&](auto M) { request(M); });
-    stats(0, 0, Lc, Dc);
+    start_dp(std::integral_constant<int, 0>{});
+    Lc = lse4(0, 0);
     static_for<0, 64>([&](auto M) {
         constexpr int m = decltype(M)::value;
         request(std::integral_constant<int, m + kAhead>{});
+        if constexpr (m < 9) copy_piece(M);
+        if constexpr (m == 10) start_dp(std::integral_constant<int, 1>{});
         if constexpr (m < 32) {
             constexpr int b = m >> 4, t = (m & 15) >> 1;
-            if constexpr (m & 1) score_mfma<kRegV + 4 * t, t == 0>(dp[b], ring[m & 7].v);  // dP = dO V^T
-            else score_mfma<kRegK + 4 * t, t == 0>(s[b], ring[m & 7].v);                     // S  = Q K^T
+            if constexpr (m & 1) score_mfma<kRegV + 4 * t, false>(dp[b], ring[m & 7].v);  // dP - delta = dO V^T - delta
+            else score_mfma<kRegK + 4 * t, t == 0>(s[b], ring[m & 7].v);                   // S = Q K^T
         } else {
             constexpr int j = (m - 32) & 15, b = (m - 32) >> 4, half = j >> 3, db = (j & 7) >> 1;
             if constexpr (j & 1) acc_mfma<kAccDK + 16 * db>(ring[m & 7].v, __builtin_bit_cast(bf16x8, dw[b][half]));
@@ -150,21 +164,21 @@ __device__ __forceinline__ void dkdv_tile(const char* sQ, const char* sG, const 
         }
         if constexpr (m >= 16 && m < 48) {
             // slot pair (2j, 2j + 1) of the phase turns accumulator elements 2j, 2j + 1 of
-            // block b into packed P (even slot) and packed dS (odd slot)
+            // block b into packed P and packed dS: the exponentials in the even slot, the
+            // rest in the odd one
             constexpr int n = m - 16, b = n >> 4, k = n & 15, j = k >> 1, i = 2 * j;
             // S of block b was finished two MFMAs ago when k = 0, dP when k = 1
             if constexpr (k < 2) settle();
-            if constexpr ((k & 3) == 0 && n + 4 < 32) stats((n + 4) >> 4, ((n + 4) & 15) >> 2, Ln, Dn);
+            if constexpr ((k & 3) == 0 && n + 4 < 32) Ln = lse4((n + 4) >> 4, ((n + 4) & 15) >> 2);
             if constexpr ((k & 1) == 0) {
                 p0 = __builtin_amdgcn_exp2f(fmaf(s[b][i], c, -comp(Lc, i & 3)));
                 p1 = __builtin_amdgcn_exp2f(fmaf(s[b][i + 1], c, -comp(Lc, (i + 1) & 3)));
-                pw[b][j >> 2][j & 3] = FULL ? pack2(p0, p1) : pack2(p0, p1) & mw[b][j];
             } else {
-                const float d0 = p0 * (dp[b][i] - comp(Dc, i & 3));
-                const float d1 = p1 * (dp[b][i + 1] - comp(Dc, (i + 1) & 3));
+                pw[b][j >> 2][j & 3] = FULL ? pack2(p0, p1) : pack2(p0, p1) & mw[b][j];
+                const float d0 = p0 * dp[b][i], d1 = p1 * dp[b][i + 1];
                 dw[b][j >> 2][j & 3] = FULL ? pack2(d0, d1) : pack2(d0, d1) & mw[b][j];
             }
-            if constexpr ((k & 3) == 3) { Lc = Ln; Dc = Dn; }
+            if constexpr ((k & 3) == 3) Lc = Ln;
         }
         __builtin_amdgcn_sched_barrier(0);
     });
@@ -174,7 +188,7 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
     __shared__ __attribute__((aligned(16))) char sQ[2][kQTileBytes];
     __shared__ __attribute__((aligned(16))) char sG[2][kQTileBytes];  // dO
     __shared__ __attribute__((aligned(16))) float sL[2][64];          // LSE * log2(e)
-    __shared__ __attribute__((aligned(16))) float sD[2][64];          // delta
+    __shared__ __attribute__((aligned(16))) float sD[2][64];          // -delta
     // a[0:191] are in use: makes the kernel's register allocation cover them
     asm volatile("" ::: "a0", "a191");
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, c32 = l & 31, g = l >> 5;
@@ -217,17 +231,30 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
     // never FULL).
     const uint32_t row_bytes = static_cast<uint32_t>(Hq) * 256u;
     const DmaLane dml = dma_lane(row_bytes, w, l);
-    auto prefetch = [&](int ent, int h, auto BUF) {
-        constexpr int buf = decltype(BUF)::value;
+    // The copy of one tile is nine instructions per lane: pieces 0-3 are Q rows, 4-7 dO rows,
+    // piece 8 the statistics.  copy_setup fixes the tile, copy_piece issues one piece.
+    const char* cp_q = nullptr;   // first Q row of the tile being copied (this head)
+    const char* cp_g = nullptr;   // first dO row
+    const float* cp_s = nullptr;  // this lane's statistic (waves 0, 1)
+    DmaLane cp_lane = dml;
+    auto copy_setup = [&](int ent, int h) {
         const int q0 = (ent >> 2) * 64;
         const size_t tile_elems = (static_cast<size_t>(q0) * Hq + h) * 128;
-        const int rmax = T - 1 - q0;
-        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.Q) + tile_elems), row_bytes, rmax, dml, sQ[buf], w, l);
-        dma_tile64(reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems), row_bytes, rmax, dml, sG[buf], w, l);
-        if (w < 2) {  // wave 0: 64 x LSE * log2 e, wave 1: 64 x delta, one dword per lane
-            const float* src = (w ? a.delta : a.lse2) + static_cast<size_t>(h) * T + q0 + min(l, rmax);
-            dma4(src, lds_addr(w ? sD[buf] : sL[buf]));
+        int rmax = T - 1 - q0;
+        cp_q = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.Q) + tile_elems);
+        cp_g = reinterpret_cast<const char*>(static_cast<const uint16_t*>(a.dO) + tile_elems);
+        cp_s = (w ? a.delta : a.lse2) + static_cast<size_t>(h) * T + q0 + min(l, rmax);
+        cp_lane = dml;
+        if (rmax < 63) {
+            asm volatile("; clipped tile" : "+s"(rmax));  // keeps the clamped offsets' arithmetic in this branch
+            cp_lane = dma_lane(row_bytes, w, l, rmax);
         }
+    };
+    auto copy_piece = [&](auto P, auto BUF) {
+        constexpr int p = decltype(P)::value, buf = decltype(BUF)::value;
+        if constexpr (p < 4) dma16(cp_q, cp_lane.off[p], lds_addr(sQ[buf]) + (16 * w + 4 * p) * kRowBytes);
+        else if constexpr (p < 8) dma16(cp_g, cp_lane.off[p - 4], lds_addr(sG[buf]) + (16 * w + 4 * (p - 4)) * kRowBytes);
+        else if (w < 2) dma4(cp_s, lds_addr(w ? sD[buf] : sL[buf]));  // wave 0: LSE * log2 e, wave 1: -delta
     };
     // Walk order: q-tiles from the last to the first, and for each q-tile the G heads
     // of the group.  Every k-tile of a sample ends at the same q-tile, so workgroups
@@ -239,7 +266,8 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
     int ent = 0, it = 0;
     if (n_it > 0) {
         ent = es.get(0);
-        prefetch(ent, kvh * G, std::integral_constant<int, 0>{});
+        copy_setup(ent, kvh * G);
+        static_for<0, 9>([&](auto P) { copy_piece(P, std::integral_constant<int, 0>{}); });
         if (++ph == G) { ph = 0; ++pk; }
     }
     // One tile; the buffer index is a compile-time constant, so every LDS address is a lane
@@ -251,18 +279,22 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
         dma_wait_barrier<0>();
         const int q0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
-        if (it + 1 < n_it) {
+        const bool more = it + 1 < n_it;
+        if (more) {
             ent = es.get(pk);
-            prefetch(ent, kvh * G + ph, std::integral_constant<int, buf ^ 1>{});
+            copy_setup(ent, kvh * G + ph);
             if (++ph == G) { ph = 0; ++pk; }
         }
         ++it;
+        auto piece = [&](auto P) {
+            if (more) copy_piece(P, std::integral_constant<int, buf ^ 1>{});
+        };
         uint32_t mw[2][8];
         if (full) {
-            dkdv_tile<true>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g);
+            dkdv_tile<true>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g, piece);
         } else {
             pair_masks(mw, key - q0, key_hi - q0, g);
-            dkdv_tile<false>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g);
+            dkdv_tile<false>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g, piece);
         }
     };
     // The K / V loads above have retired before the loop starts, so the loop body holds no
