@@ -167,8 +167,9 @@ __device__ __forceinline__ void dkdv_tile(const char* sQ, const char* sG, const 
             // block b into packed P and packed dS: the exponentials in the even slot, the
             // rest in the odd one
             constexpr int n = m - 16, b = n >> 4, k = n & 15, j = k >> 1, i = 2 * j;
-            // S of block b was finished two MFMAs ago when k = 0, dP when k = 1
-            if constexpr (k < 2) settle();
+            // No wait states are needed here: the chain that produced S of block b (k = 0) or dP
+            // (k = 1) ended three slots ago, and the two MFMAs issued since then each held the
+            // matrix pipeline for as long as an MFMA takes to finish.
             if constexpr ((k & 3) == 0 && n + 4 < 32) Ln = lse4((n + 4) >> 4, ((n + 4) & 15) >> 2);
             if constexpr ((k & 1) == 0) {
                 p0 = __builtin_amdgcn_exp2f(fmaf(s[b][i], c, -comp(Lc, i & 3)));
@@ -279,16 +280,15 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
         dma_wait_barrier<0>();
         const int q0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
-        const bool more = it + 1 < n_it;
-        if (more) {
+        // After the last tile the copy is issued once more (same tile, other buffer): the slots
+        // then need no branch around each piece; nobody reads that buffer.
+        if (it + 1 < n_it) {
             ent = es.get(pk);
             copy_setup(ent, kvh * G + ph);
             if (++ph == G) { ph = 0; ++pk; }
         }
         ++it;
-        auto piece = [&](auto P) {
-            if (more) copy_piece(P, std::integral_constant<int, buf ^ 1>{});
-        };
+        auto piece = [&](auto P) { copy_piece(P, std::integral_constant<int, buf ^ 1>{}); };
         uint32_t mw[2][8];
         if (full) {
             dkdv_tile<true>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g, piece);
@@ -305,6 +305,8 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
         if (it & 1) tile(std::integral_constant<int, 1>{});
         else tile(std::integral_constant<int, 0>{});
     }
+    // no copy may still be writing to LDS when the workgroup ends
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     settle();  // the last MFMAs, before dK / dV are read out
     if (kvalid) {
         uint16_t* krow = static_cast<uint16_t*>(a.dK) + koff;
