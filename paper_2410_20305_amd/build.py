@@ -27,6 +27,17 @@ def hipcc() -> str:
     return "hipcc"
 
 
+def device_asm(src: str, out: str) -> str:
+    """Compiles one source of csrc/ to gfx950 assembly with the library's own flags (for
+    checks on register use); returns the text."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-x", "hip", "-I", os.path.join(ROOT, "include"),
+           "-I", CSRC, *DEVICE_FLAGS, *SOURCE_FLAGS.get(src, []), "-S", "--cuda-device-only", "-w",
+           os.path.join(CSRC, src), "-o", out]
+    subprocess.check_call(cmd)
+    with open(out) as f:
+        return f.read()
+
+
 def build(verbose: bool = True, extra=()) -> str:
     """Always recompiles; returns the path of the shared library."""
     objs = []
