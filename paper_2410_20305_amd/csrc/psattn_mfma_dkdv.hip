@@ -283,8 +283,14 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
         // After the last tile the copy is issued once more (same tile, other buffer): the slots
         // then need no branch around each piece; nobody reads that buffer.
         if (it + 1 < n_it) {
-            ent = es.get(pk);
-            copy_setup(ent, kvh * G + ph);
+            if (ph == 0) {  // first head of the next q-tile
+                ent = es.get(pk);
+                copy_setup(ent, kvh * G);
+            } else {        // same q-tile, next head of the group: 128 elements / T statistics further on
+                cp_q += 256;
+                cp_g += 256;
+                cp_s += T;
+            }
             if (++ph == G) { ph = 0; ++pk; }
         }
         ++it;
