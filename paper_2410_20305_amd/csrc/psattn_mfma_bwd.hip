@@ -68,11 +68,11 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     // buffer the previous tile has just vacated; one barrier per tile.
     const uint32_t row_bytes = static_cast<uint32_t>(Hkv) * 256u;
     const DmaLane dml = dma_lane(row_bytes, w, l);
-    auto fetch = [&](int ent, auto BUF) {
-        constexpr int buf = decltype(BUF)::value;
+    PairCopy pc;
+    auto copy_setup = [&](int ent) {
         const int k0 = (ent >> 2) * 64;
-        dma_tile64(reinterpret_cast<const char*>(K) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dml, sKb[buf], w, l);
-        dma_tile64(reinterpret_cast<const char*>(V) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dml, sVb[buf], w, l);
+        pair_copy_setup(pc, reinterpret_cast<const char*>(K) + static_cast<size_t>(k0) * row_bytes,
+                        reinterpret_cast<const char*>(V) + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dml, w, l);
     };
     const int e0 = csr.row_ptr[qt], n_ent = csr.row_ptr[qt + 1] - e0;
     EntryStream es;
@@ -80,7 +80,8 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     int ent = 0, it = 0;
     if (n_ent > 0) {
         ent = es.get(0);
-        fetch(ent, std::integral_constant<int, 0>{});
+        copy_setup(ent);
+        static_for<0, 8>([&](auto P) { pair_copy_piece<decltype(P)::value>(pc, sKb[0], sVb[0], w); });
     }
     const LaneOffsets lo = lane_offsets(l);
     constexpr int kAhead = 3, kRing = 4;
@@ -120,6 +121,7 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
             static_for<0, 16>([&](auto J) {
                 constexpr int j = decltype(J)::value, m = 24 * kb + j, t = j >> 1;
                 request(std::integral_constant<int, m + kAhead>{});
+                if constexpr (m < 8) pair_copy_piece<m>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w);
                 if constexpr (j & 1) dp = mfma(ring[m % kRing].v, gf[t].v, dp);
                 else s = mfma(ring[m % kRing].v, qf[t].v, s);
                 __builtin_amdgcn_sched_barrier(0);
@@ -160,9 +162,12 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
         dma_wait_barrier<0>();
         const int k0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
+        // The next tile's copy is issued piece by piece in the first eight slots of the tile.
+        // After the last tile the same tile is copied once more (to the other buffer, which
+        // nobody reads), so the slots need no branch.
         if (it + 1 < n_ent) {
             ent = es.get(it + 1);
-            fetch(ent, std::integral_constant<int, buf ^ 1>{});
+            copy_setup(ent);
         }
         ++it;
         tile(BUF, k0, full);
@@ -175,6 +180,8 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
         step(std::integral_constant<int, 1>{});
     }
     if (it < n_ent) step(std::integral_constant<int, 0>{});
+    // no copy may still be writing to LDS when the workgroup ends
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (valid) {
         uint16_t* row = static_cast<uint16_t*>(a.dQ) + qoff;
         const float sc = a.scale;

@@ -215,6 +215,33 @@ __device__ __forceinline__ void dma_tile64(const char* base, uint32_t row_bytes,
     }
 }
 
+// Copy of a pair of tiles (K and V of one key block, or Q and dO of one query block) as
+// eight separate instructions per lane, so that a kernel can spread them over its MFMA
+// slots: issued back to back they hold the wave for about a thousand cycles.
+// Pieces 0-3 belong to the first tile, 4-7 to the second.
+struct PairCopy {
+    const char* a;  // first row of the first tile (wave-uniform)
+    const char* b;  // first row of the second tile
+    DmaLane lane;
+};
+
+__device__ __forceinline__ void pair_copy_setup(PairCopy& c, const char* a, const char* b, uint32_t row_bytes, int last_row,
+                                                const DmaLane& full, int w, int l) {
+    c.a = a;
+    c.b = b;
+    c.lane = full;
+    if (last_row < 63) {
+        asm volatile("; clipped tile" : "+s"(last_row));  // keeps the clamped offsets' arithmetic in this branch
+        c.lane = dma_lane(row_bytes, w, l, last_row);
+    }
+}
+
+template <int P>
+__device__ __forceinline__ void pair_copy_piece(const PairCopy& c, const char* tile_a, const char* tile_b, int w) {
+    if constexpr (P < 4) dma16(c.a, c.lane.off[P], lds_addr(tile_a) + (16 * w + 4 * P) * kRowBytes);
+    else dma16(c.b, c.lane.off[P - 4], lds_addr(tile_b) + (16 * w + 4 * (P - 4)) * kRowBytes);
+}
+
 // Reader of a tile list walked in one direction: position k = 0, 1, ... maps to
 // list[first + step * k] (step = +1 or -1), n positions in all.  Lane l keeps entry
 // 64 b + l of the current batch b; the next batch is requested when a batch is entered,

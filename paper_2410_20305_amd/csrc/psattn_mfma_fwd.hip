@@ -49,11 +49,11 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
     const char* Kb = reinterpret_cast<const char*>(K);
     const char* Vb = reinterpret_cast<const char*>(V);
     const DmaLane dl = dma_lane(row_bytes, w, l);
-    auto fetch = [&](int ent, auto BUF) {
-        constexpr int buf = decltype(BUF)::value;
+    PairCopy pc;
+    auto copy_setup = [&](int ent) {
         const int k0 = (ent >> 2) * 64;
-        dma_tile64(Kb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dl, sKb[buf], w, l);
-        dma_tile64(Vb + static_cast<size_t>(k0) * row_bytes, row_bytes, T - 1 - k0, dl, sVb[buf], w, l);
+        pair_copy_setup(pc, Kb + static_cast<size_t>(k0) * row_bytes, Vb + static_cast<size_t>(k0) * row_bytes, row_bytes,
+                        T - 1 - k0, dl, w, l);
     };
     const int e0 = csr.row_ptr[qt], n_ent = csr.row_ptr[qt + 1] - e0;
     EntryStream es;
@@ -61,7 +61,8 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
     int ent = 0, it = 0;
     if (n_ent > 0) {
         ent = es.get(0);
-        fetch(ent, std::integral_constant<int, 0>{});
+        copy_setup(ent);
+        static_for<0, 8>([&](auto P) { pair_copy_piece<decltype(P)::value>(pc, sKb[0], sVb[0], w); });
     }
     // One tile.  The buffer index is a compile-time constant (the loop below is unrolled
     // by two), so every LDS address is a lane constant plus an immediate offset.
@@ -72,9 +73,12 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         dma_wait_barrier<0>();
         const int k0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
+        // The next tile's copy is issued piece by piece in the first eight slots below.  After
+        // the last tile the same tile is copied once more (to the other buffer, which nobody
+        // reads), so the slots need no branch.
         if (it + 1 < n_ent) {
             ent = es.get(it + 1);
-            fetch(ent, std::integral_constant<int, buf ^ 1>{});
+            copy_setup(ent);
         }
         ++it;
         const char* sK = sKb[buf];
@@ -102,6 +106,7 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         static_for<0, 16>([&](auto M) {
             constexpr int m = decltype(M)::value, t = m >> 1, kb = m & 1;
             request(std::integral_constant<int, m + kAhead>{});
+            if constexpr (m < 8) pair_copy_piece<m>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w);
             s[kb] = mfma(ring[m % kRing].v, qf[t].v, s[kb]);
             __builtin_amdgcn_sched_barrier(0);
         });
@@ -170,6 +175,8 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         tile(std::integral_constant<int, 1>{});
     }
     if (it < n_ent) tile(std::integral_constant<int, 0>{});
+    // no copy may still be writing to LDS when the workgroup ends
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     const float l_tot = lsum + other_half(lsum);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (valid) {
