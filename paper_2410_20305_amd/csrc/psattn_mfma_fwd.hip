@@ -121,11 +121,13 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
                     s[kb][i] = ok ? s[kb][i] : -INFINITY;
                 }
         }
-        float mx = s[0][0];
+        // four independent chains each for the maximum and (below) the sum
+        float mxp[4];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int r = 0; r < 4; ++r) mxp[r] = fmaxf(s[0][r], s[1][r]);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[kb][i]);
+        for (int i = 4; i < 16; ++i) mxp[i & 3] = fmaxf(mxp[i & 3], fmaxf(s[0][i], s[1][i]));
+        float mx = fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3]));
         mx = fmaxf(mx, other_half(mx));
         // The reference maximum m only has to keep exp2 in range: it moves when the new
         // maximum exceeds it by more than kSlack (base-2 exponent units).  kSlack = 0 is the
@@ -146,18 +148,19 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
             m = m_new;
         }
         const float m_use = m == -INFINITY ? 0.f : m;
-        float psum = 0.f;
+        float ps[4] = {0.f, 0.f, 0.f, 0.f};
         bf16x8 pb[2][2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
                 s[kb][i] = __builtin_amdgcn_exp2f(fmaf(s[kb][i], c, -m_use));
-                psum += s[kb][i];
+                ps[i & 3] += s[kb][i];
             }
             pb[kb][0] = pack8(s[kb], 0);
             pb[kb][1] = pack8(s[kb], 1);
         }
+        const float psum = (ps[0] + ps[1]) + (ps[2] + ps[3]);
         lsum += psum;
         __builtin_amdgcn_sched_barrier(0);
         static_for<16, 32>([&](auto M) {
