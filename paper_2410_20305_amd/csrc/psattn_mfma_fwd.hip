@@ -124,11 +124,15 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         // four independent chains each for the maximum and (below) the sum
         float mxp[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mxp[r] = fmaxf(s[0][r], s[1][r]);
+        for (int r = 0; r < 4; ++r) mxp[r] = max3(s[0][r], s[1][r], s[0][r + 4]);
 #pragma unroll
-        for (int i = 4; i < 16; ++i) mxp[i & 3] = fmaxf(mxp[i & 3], fmaxf(s[0][i], s[1][i]));
-        float mx = fmaxf(fmaxf(mxp[0], mxp[1]), fmaxf(mxp[2], mxp[3]));
-        mx = fmaxf(mx, other_half(mx));
+        for (int r = 0; r < 4; ++r) mxp[r] = max3(mxp[r], s[1][r + 4], s[0][r + 8]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mxp[r] = max3(mxp[r], s[1][r + 8], s[0][r + 12]);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) mxp[r] = max3(mxp[r], s[1][r + 12], mxp[r]);
+        float mx = max3(mxp[0], mxp[1], max3(mxp[2], mxp[3], mxp[3]));
+        mx = max3(mx, other_half(mx), mx);
         // The reference maximum m only has to keep exp2 in range: it moves when the new
         // maximum exceeds it by more than kSlack (base-2 exponent units).  kSlack = 0 is the
         // exact running maximum.  A slack of 8 makes rescaling rare and saves about 5 % of
