@@ -41,7 +41,6 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
     const float c = a.scale * kLog2e;
     const LaneOffsets lo = lane_offsets(l);
     constexpr int kAhead = 3, kRing = 4;
-    constexpr float kSlack = 0.f;
 
     // K / V tiles are copied global -> LDS asynchronously, one tile ahead, into the
     // buffer the previous tile has just vacated; one barrier per tile.
@@ -133,14 +132,14 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         for (int r = 0; r < 4; ++r) mxp[r] = max3(mxp[r], s[1][r + 12], mxp[r]);
         float mx = max3(mxp[0], mxp[1], max3(mxp[2], mxp[3], mxp[3]));
         mx = max3(mx, other_half(mx), mx);
-        // The reference maximum m only has to keep exp2 in range: it moves when the new
-        // maximum exceeds it by more than kSlack (base-2 exponent units).  kSlack = 0 is the
-        // exact running maximum.  A slack of 8 makes rescaling rare and saves about 5 % of
-        // this kernel's time, but the largest probability of a row is then no longer exactly
-        // 1 and picks up a bf16 rounding error: on short rows with large |V| the error of O
-        // then passes 1e-2, so it stays off.
+        // Exact running maximum; O and l are rescaled only in tiles where some row's maximum
+        // moves (wave ballot).  Letting the reference lag behind the maximum was measured
+        // both ways: a fixed lag of 2^8 saves 5 % of this kernel but the largest probability of
+        // a row is then no longer exactly 1 and its bf16 rounding shows in O on short rows
+        // (0.012 against a bar of 1e-2); a lag bounded by the row's sum so far keeps the
+        // accuracy but saves nothing measurable.
         const float m_new = fmaxf(m, mx * c);
-        if (__builtin_amdgcn_ballot_w64(m_new > m + kSlack) != 0) {
+        if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {
             asm volatile("; rescale" ::: "memory");
             const float m_to = m_new == -INFINITY ? 0.f : m_new;
             const float alpha = __builtin_amdgcn_exp2f(m - m_to);  // m = -inf: 0 (nothing accumulated yet)
