@@ -127,16 +127,14 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
                 __builtin_amdgcn_sched_barrier(0);
             });
             if (!full) {
-                // key index of accumulator element i: jb + 8 (i / 4) + i % 4; the statement below
-                // keeps the sixteen sums from being kept in registers across the whole loop
-                int jb = k0 + 32 * kb + 4 * g;
-                asm volatile("; mask of a PARTIAL tile" : "+v"(jb));
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int j = jb + 8 * (i >> 2) + (i & 3);
-                    const bool ok = (j >= tk.s) & (j <= q_row) & !((j >= tk.hole_lo) & (j < tk.hole_hi));
-                    s[i] = ok ? s[i] : -INFINITY;  // p = 0 below
-                }
+                asm volatile("; mask of a PARTIAL tile" ::: "memory");
+                // this query reads keys [tk.s, q_row] except [hole_lo, hole_hi); p = 0 below
+                const uint32_t bits = elem_range_bits(tk.s - k0, q_row + 1 - k0, g) &
+                                      ~elem_range_bits(tk.hole_lo - k0, tk.hole_hi - k0, g);
+                static_for<0, 16>([&](auto I) {
+                    constexpr int i = decltype(I)::value;
+                    s[i] = keep_or_neg_inf<16 * kb + i>(s[i], bits);
+                });
             }
 #pragma unroll
             for (int i = 0; i < 16; ++i) {

@@ -125,6 +125,27 @@ __device__ __forceinline__ bf16x8 ld_cols(const char* blk, int tr1, int tr2) {
     return f.v;
 }
 
+// Mask arithmetic of PARTIAL tiles.  A lane's 32 score elements of a 64-row tile are
+// numbered e = 16 b + i (b = 32-row block, i = accumulator register); element e belongs to
+// tile row 32 b + acc_row(i, g), so the elements ordered by e are also ordered by row.
+// elems_below(x, g): how many of them lie in rows below x, 0 <= x <= 64.
+__device__ inline int elems_below(int x, int g) {
+    return 4 * (x >> 3) + min(max((x & 7) - 4 * g, 0), 4);
+}
+
+// bit e set <=> element e lies in tile rows [lo, hi) (any integers; clamped to the tile)
+__device__ inline uint32_t elem_range_bits(int lo, int hi, int g) {
+    const int a = elems_below(min(max(lo, 0), 64), g), b = elems_below(min(max(hi, 0), 64), g);
+    return static_cast<uint32_t>(((1ull << b) - 1) & ~((1ull << a) - 1));
+}
+
+// x if bit e of `bits` is set, otherwise -inf (two instructions: bit -> word mask, select)
+template <int E>
+__device__ __forceinline__ float keep_or_neg_inf(float x, uint32_t bits) {
+    const uint32_t m = static_cast<uint32_t>(static_cast<int32_t>(bits << (31 - E)) >> 31);
+    return __uint_as_float((__float_as_uint(x) & m) | (~m & 0xff800000u));
+}
+
 // max(a, b, c) in one instruction.  (fmaxf makes the compiler quiet possible signalling
 // NaNs with an extra v_max per operand; scores are never NaN.)
 __device__ __forceinline__ float max3(float a, float b, float c) {

@@ -77,17 +77,10 @@ __device__ __forceinline__ void settle() {
 constexpr int kQTileBytes = 64 * kRowBytes;
 constexpr int kAhead = 5;
 
-// Number of accumulator elements e = 16 b + i (b = 32-query block, i = register) of
-// lane-half g whose tile row 32 b + acc_row(i, g) lies below x, 0 <= x <= 64.
-__device__ inline int elems_below(int x, int g) {
-    return 4 * (x >> 3) + min(max((x & 7) - 4 * g, 0), 4);
-}
-
 // AND-masks for the packed bf16 pairs (elements 2j, 2j + 1 of block b) of one q-tile:
 // the queries allowed to read this lane's key are rows [lo, hi) of the tile.
 __device__ inline void pair_masks(uint32_t (&mw)[2][8], int lo, int hi, int g) {
-    const int a = elems_below(min(max(lo, 0), 64), g), b = elems_below(min(max(hi, 0), 64), g);
-    const uint32_t bits = static_cast<uint32_t>(((1ull << b) - 1) & ~((1ull << a) - 1));
+    const uint32_t bits = elem_range_bits(lo, hi, g);
 #pragma unroll
     for (int b2 = 0; b2 < 2; ++b2)
 #pragma unroll

@@ -111,14 +111,13 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         });
         if (!full) {
             asm volatile("; mask of a PARTIAL tile" ::: "memory");
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int j = k0 + 32 * kb + acc_row(i, g);
-                    const bool ok = (j >= tk.s) & (j <= q_row) & !((j >= tk.hole_lo) & (j < tk.hole_hi));
-                    s[kb][i] = ok ? s[kb][i] : -INFINITY;
-                }
+            // this query reads keys [tk.s, q_row] except [hole_lo, hole_hi)
+            const uint32_t bits = elem_range_bits(tk.s - k0, q_row + 1 - k0, g) &
+                                  ~elem_range_bits(tk.hole_lo - k0, tk.hole_hi - k0, g);
+            static_for<0, 32>([&](auto E) {
+                constexpr int e = decltype(E)::value;
+                s[e >> 4][e & 15] = keep_or_neg_inf<e>(s[e >> 4][e & 15], bits);
+            });
         }
         // four independent chains each for the maximum and (below) the sum
         float mxp[4];
