@@ -121,7 +121,7 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
             static_for<0, 16>([&](auto J) {
                 constexpr int j = decltype(J)::value, m = 24 * kb + j, t = j >> 1;
                 request(std::integral_constant<int, m + kAhead>{});
-                if constexpr (m < 8) pair_copy_piece<m>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w);
+                if constexpr (m < 16 && (m & 1) == 0) pair_copy_piece<m / 2>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w);  // every other slot: see PairCopy
                 if constexpr (j & 1) dp = mfma(ring[m % kRing].v, gf[t].v, dp);
                 else s = mfma(ring[m % kRing].v, qf[t].v, s);
                 __builtin_amdgcn_sched_barrier(0);

@@ -246,7 +246,9 @@ __device__ __forceinline__ void dma_tile64(const char* base, uint32_t row_bytes,
 
 // Copy of a pair of tiles (K and V of one key block, or Q and dO of one query block) as
 // eight separate instructions per lane, so that a kernel can spread them over its MFMA
-// slots: issued back to back they hold the wave for about a thousand cycles.
+// slots: issued back to back they hold the wave for about a thousand cycles (the CU's
+// address unit takes one such instruction per ~16 cycles and the waves of a workgroup issue
+// theirs at the same moment).  One piece every other slot keeps the unit's queue short.
 // Pieces 0-3 belong to the first tile, 4-7 to the second.
 struct PairCopy {
     const char* a;  // first row of the first tile (wave-uniform)

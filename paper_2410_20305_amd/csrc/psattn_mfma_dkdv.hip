@@ -101,7 +101,7 @@ __device__ inline float comp(const float4& v, int i) { return i == 0 ? v.x : i =
 
 // FULL: every pair of the tile is allowed, no mask work at all (mw is not read).
 // copy_piece(k), k = 0 .. 8, issues one instruction of the next tile's asynchronous copy;
-// the pieces are spread over the first slots, whose only other work is MFMAs.
+// the pieces are spread over the first slots.
 template <bool FULL, typename CopyPiece>
 __device__ __forceinline__ void dkdv_tile(const char* sQ, const char* sG, const float* sL, const float* sD,
                                           const LaneOffsets& lo, const uint32_t (&mw)[2][8], float c, int g,
@@ -144,8 +144,14 @@ __device__ __forceinline__ void dkdv_tile(const char* sQ, const char* sG, const 
     static_for<0, 64>([&](auto M) {
         constexpr int m = decltype(M)::value;
         request(std::integral_constant<int, m + kAhead>{});
-        if constexpr (m < 9) copy_piece(M);
+        // Copy pieces go out every other slot: the four waves issue theirs at the same moment and
+        // the CU's address unit takes one such instruction per ~16 cycles, so a piece per slot
+        // from each wave would queue up and stall the waves.
+        if constexpr (m < 18 && (m & 1) == 0) copy_piece(std::integral_constant<int, m / 2>{});
         if constexpr (m == 10) start_dp(std::integral_constant<int, 1>{});
+        // One wait per two slots: naming the next slot's operand here makes the compiler wait
+        // for both now (the statement itself is empty), and the odd slot then needs none.
+        if constexpr ((m & 1) == 0) asm volatile("" ::"v"(ring[(m + 1) & 7].v));
         if constexpr (m < 32) {
             constexpr int b = m >> 4, t = (m & 15) >> 1;
             if constexpr (m & 1) score_mfma<kRegV + 4 * t, false>(dp[b], ring[m & 7].v);  // dP - delta = dO V^T - delta

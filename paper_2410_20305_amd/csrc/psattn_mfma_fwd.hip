@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         static_for<0, 16>([&](auto M) {
             constexpr int m = decltype(M)::value, t = m >> 1, kb = m & 1;
             request(std::integral_constant<int, m + kAhead>{});
-            if constexpr (m < 8) pair_copy_piece<m>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w);
+            if constexpr ((m & 1) == 0) pair_copy_piece<m / 2>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w);  // every other slot: see PairCopy
             s[kb] = mfma(ring[m % kRing].v, qf[t].v, s[kb]);
             __builtin_amdgcn_sched_barrier(0);
         });
