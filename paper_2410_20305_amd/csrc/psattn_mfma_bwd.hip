@@ -96,6 +96,18 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     // Only PARTIAL tiles (full == false) run the mask arithmetic.
     auto tile = [&](auto BUF, int k0, bool full) {
         constexpr int buf = decltype(BUF)::value;
+        // PARTIAL tile: this lane's allowed elements as a bit mask (the query reads keys
+        // [tk.s, q_row] except [hole_lo, hole_hi)).  A wave none of whose 32 queries reads any
+        // key of the tile only issues its share of the copy and leaves the SIMD to the other
+        // workgroup's wave.
+        uint32_t bits = 0xffffffffu;
+        if (!full) {
+            bits = elem_range_bits(tk.s - k0, q_row + 1 - k0, g) & ~elem_range_bits(tk.hole_lo - k0, tk.hole_hi - k0, g);
+            if (__builtin_amdgcn_ballot_w64(bits != 0) == 0) {
+                static_for<0, 8>([&](auto P) { pair_copy_piece<decltype(P)::value>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w); });
+                return;
+            }
+        }
         const char* sK = sKb[buf];
         const char* sV = sVb[buf];
         Frag8 ring[kRing];
@@ -128,9 +140,7 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
             });
             if (!full) {
                 asm volatile("; mask of a PARTIAL tile" ::: "memory");
-                // this query reads keys [tk.s, q_row] except [hole_lo, hole_hi); p = 0 below
-                const uint32_t bits = elem_range_bits(tk.s - k0, q_row + 1 - k0, g) &
-                                      ~elem_range_bits(tk.hole_lo - k0, tk.hole_hi - k0, g);
+                // masked scores become -inf, so p = 0 below
                 static_for<0, 16>([&](auto I) {
                     constexpr int i = decltype(I)::value;
                     s[i] = keep_or_neg_inf<16 * kb + i>(s[i], bits);

@@ -80,6 +80,18 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
             copy_setup(ent);
         }
         ++it;
+        // PARTIAL tile: this lane's allowed elements as a bit mask (the query reads keys
+        // [tk.s, q_row] except [hole_lo, hole_hi)).  A wave none of whose 32 queries reads any
+        // key of the tile only issues its share of the copy and leaves the SIMD to the other
+        // workgroup's wave (two of the four waves on the second tile of every causal diagonal).
+        uint32_t bits = 0xffffffffu;
+        if (!full) {
+            bits = elem_range_bits(tk.s - k0, q_row + 1 - k0, g) & ~elem_range_bits(tk.hole_lo - k0, tk.hole_hi - k0, g);
+            if (__builtin_amdgcn_ballot_w64(bits != 0) == 0) {
+                static_for<0, 8>([&](auto P) { pair_copy_piece<decltype(P)::value>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w); });
+                return;
+            }
+        }
         const char* sK = sKb[buf];
         const char* sV = sVb[buf];
         // 32 MFMA slots per tile: 0-15 S^T = K Q^T (rows = keys, column = this lane's
@@ -111,9 +123,6 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         });
         if (!full) {
             asm volatile("; mask of a PARTIAL tile" ::: "memory");
-            // this query reads keys [tk.s, q_row] except [hole_lo, hole_hi)
-            const uint32_t bits = elem_range_bits(tk.s - k0, q_row + 1 - k0, g) &
-                                  ~elem_range_bits(tk.hole_lo - k0, tk.hole_hi - k0, g);
             static_for<0, 32>([&](auto E) {
                 constexpr int e = decltype(E)::value;
                 s[e >> 4][e & 15] = keep_or_neg_inf<e>(s[e >> 4][e & 15], bits);
