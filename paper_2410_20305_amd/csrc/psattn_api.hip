@@ -15,7 +15,7 @@ namespace {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 struct BlobLayout {
-    size_t tok, f_row, f_ent, f_ord, b_row, b_ent, b_ord, total;
+    size_t tok, f_row, f_ent, f_ord, f_lch, b_row, b_ent, b_ord, b_lch, total;
 };
 
 BlobLayout layout_of(const psattn_meta& m) {
@@ -26,25 +26,34 @@ BlobLayout layout_of(const psattn_meta& m) {
     L.f_row = take(sizeof(int32_t) * m.fwd.row_ptr.size());
     L.f_ent = take(sizeof(int32_t) * m.fwd.idx.size());
     L.f_ord = take(sizeof(int32_t) * m.fwd.order.size());
+    L.f_lch = take(sizeof(RowLaunch) * m.fwd.order.size());
     L.b_row = take(sizeof(int32_t) * m.bwd.row_ptr.size());
     L.b_ent = take(sizeof(int32_t) * m.bwd.idx.size());
     L.b_ord = take(sizeof(int32_t) * m.bwd.order.size());
+    L.b_lch = take(sizeof(RowLaunch) * m.bwd.order.size());
     L.total = off ? off : 256;
     return L;
 }
 
-void fill_csr(char* base, size_t row, size_t ent, size_t ord, const TileCsr& g) {
+// walk_backwards: the kernel of this grid starts with the last entry of a row
+void fill_csr(char* base, size_t row, size_t ent, size_t ord, size_t lch, const TileCsr& g, bool walk_backwards) {
     std::memcpy(base + row, g.row_ptr.data(), g.row_ptr.size() * sizeof(int32_t));
     int32_t* e = reinterpret_cast<int32_t*>(base + ent);
     for (size_t i = 0; i < g.idx.size(); ++i) e[i] = (g.idx[i] << 2) | g.cls[i];
     std::memcpy(base + ord, g.order.data(), g.order.size() * sizeof(int32_t));
+    RowLaunch* rl = reinterpret_cast<RowLaunch*>(base + lch);
+    for (size_t i = 0; i < g.order.size(); ++i) {
+        const int32_t r = g.order[i], b = g.row_ptr[r], n = g.row_ptr[r + 1] - b;
+        rl[i] = RowLaunch{r, b, n, n > 0 ? e[walk_backwards ? b + n - 1 : b] : 0};
+    }
 }
 
-DeviceCsr view_csr(const char* base, size_t row, size_t ent, size_t ord, const TileCsr& g) {
+DeviceCsr view_csr(const char* base, size_t row, size_t ent, size_t ord, size_t lch, const TileCsr& g) {
     DeviceCsr v{};
     v.row_ptr = reinterpret_cast<const int32_t*>(base + row);
     v.entry = reinterpret_cast<const int32_t*>(base + ent);
     v.order = reinterpret_cast<const int32_t*>(base + ord);
+    v.launch = reinterpret_cast<const RowLaunch*>(base + lch);
     v.n_rows = static_cast<int32_t>(g.row_ptr.size()) - 1;
     v.tile_q = g.tile_q;
     v.tile_k = g.tile_k;
@@ -69,8 +78,8 @@ int upload(psattn_meta* m, hipStream_t stream) {
     Tok4* tok = reinterpret_cast<Tok4*>(h + L.tok);
     for (int32_t t = 0; t < m->T; ++t)
         tok[t] = Tok4{m->tok_desc[3 * t], m->tok_desc[3 * t + 1], m->tok_desc[3 * t + 2], m->key_hi[t]};
-    fill_csr(h, L.f_row, L.f_ent, L.f_ord, m->fwd);
-    fill_csr(h, L.b_row, L.b_ent, L.b_ord, m->bwd);
+    fill_csr(h, L.f_row, L.f_ent, L.f_ord, L.f_lch, m->fwd, false);
+    fill_csr(h, L.b_row, L.b_ent, L.b_ord, L.b_lch, m->bwd, true);
     if (hipMemcpyAsync(m->d_blob, h, L.total, hipMemcpyHostToDevice, stream) != hipSuccess) {
         (void)hipGetLastError();
         return PSATTN_EHIP;
@@ -78,8 +87,8 @@ int upload(psattn_meta* m, hipStream_t stream) {
     const char* d = static_cast<const char*>(m->d_blob);
     m->blob_bytes = L.total;
     m->dev.tok = reinterpret_cast<const Tok4*>(d + L.tok);
-    m->dev.fwd = view_csr(d, L.f_row, L.f_ent, L.f_ord, m->fwd);
-    m->dev.bwd = view_csr(d, L.b_row, L.b_ent, L.b_ord, m->bwd);
+    m->dev.fwd = view_csr(d, L.f_row, L.f_ent, L.f_ord, L.f_lch, m->fwd);
+    m->dev.bwd = view_csr(d, L.b_row, L.b_ent, L.b_ord, L.b_lch, m->bwd);
     m->dev.T = m->T;
     m->on_device = true;
     return PSATTN_OK;

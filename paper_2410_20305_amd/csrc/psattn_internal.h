@@ -27,11 +27,23 @@ struct TileCsr {
     std::vector<int32_t> order;    // rows sorted by decreasing work (longest first)
 };
 
+// What a workgroup of the MFMA kernels needs to start on its row, in launch order: one
+// 16-byte scalar load instead of a chain of three dependent ones (launch order -> row ->
+// list bounds -> first entry), which is a noticeable part of a short workgroup's life.
+struct alignas(16) RowLaunch {
+    int32_t row;          // tile row (q-tile for the q-major grid, k-tile for the k-major one)
+    int32_t begin;        // first position of the row's tile list in `entry`
+    int32_t count;        // its length
+    int32_t first_entry;  // the entry the walk starts with: entry[begin] for the q-major grid,
+                          // entry[begin + count - 1] for the k-major one (walked backwards)
+};
+
 // Device-side view handed to kernels by value.
 struct DeviceCsr {
     const int32_t* row_ptr;
     const int32_t* entry;  // (idx << 2) | cls
     const int32_t* order;
+    const RowLaunch* launch;  // [n_rows], in launch order
     int32_t n_rows;
     int32_t tile_q, tile_k;
 };

@@ -194,7 +194,8 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
     const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), l = tid & 63, c32 = l & 31, g = l >> 5;
     const int T = a.meta.T, Hq = a.Hq, Hkv = a.Hkv, G = Hq / Hkv;
     const DeviceCsr& csr = a.meta.bwd;
-    const int kvh = blockIdx.x % Hkv, kt = csr.order[blockIdx.x / Hkv];
+    const RowLaunch rl = csr.launch[blockIdx.x / Hkv];  // one scalar load: row, list bounds, first entry
+    const int kvh = blockIdx.x % Hkv, kt = rl.row;
     const int key = kt * 128 + 32 * w + c32;
     const bool kvalid = key < T;
     const int key_hi = kvalid ? a.meta.tok[key].key_hi : 0;  // queries [key, key_hi) read this key
@@ -221,7 +222,7 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
 
     const float c = a.scale * kLog2e;
     const LaneOffsets lo = lane_offsets(l);
-    const int e0 = csr.row_ptr[kt], n_ent = csr.row_ptr[kt + 1] - e0;
+    const int e0 = rl.begin, n_ent = rl.count;
     const int n_it = n_ent * G;
 
     // Staging of one q-tile (64 rows x 256 B of Q and of dO, 64 LSE * log2 e, 64 delta):
@@ -265,7 +266,7 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
     int pk = 0, ph = 0;  // walk position and head (within the group) of the next tile
     int ent = 0, it = 0;
     if (n_it > 0) {
-        ent = es.get(0);
+        ent = rl.first_entry;
         copy_setup(ent, kvh * G);
         static_for<0, 9>([&](auto P) { copy_piece(P, std::integral_constant<int, 0>{}); });
         if (++ph == G) { ph = 0; ++pk; }

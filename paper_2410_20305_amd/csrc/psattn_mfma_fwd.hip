@@ -15,7 +15,8 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
     const DeviceCsr& csr = a.meta.fwd;
     // heads of one kv group are neighbours in launch order and share an XCD when Hkv == 8
     const int kvh = blockIdx.x % Hkv, rest = blockIdx.x / Hkv;
-    const int h = kvh * G + rest % G, qt = csr.order[rest / G];
+    const RowLaunch rl = csr.launch[rest / G];  // one scalar load: row, list bounds, first entry
+    const int h = kvh * G + rest % G, qt = rl.row;
     const int q_row = qt * 128 + 32 * w + c32;
     const bool valid = q_row < T;
     Tok4 tk = {kPadStart, 0, 0, 0};
@@ -54,12 +55,12 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         pair_copy_setup(pc, Kb + static_cast<size_t>(k0) * row_bytes, Vb + static_cast<size_t>(k0) * row_bytes, row_bytes,
                         T - 1 - k0, dl, w, l);
     };
-    const int e0 = csr.row_ptr[qt], n_ent = csr.row_ptr[qt + 1] - e0;
+    const int e0 = rl.begin, n_ent = rl.count;
     EntryStream es;
     es.init(csr.entry, e0, 1, n_ent, l);
     int ent = 0, it = 0;
     if (n_ent > 0) {
-        ent = es.get(0);
+        ent = rl.first_entry;
         copy_setup(ent);
         static_for<0, 8>([&](auto P) { pair_copy_piece<decltype(P)::value>(pc, sKb[0], sVb[0], w); });
     }
