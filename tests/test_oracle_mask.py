@@ -7,6 +7,7 @@ and the earlier rejected tokens), against closed-form pair counts, and against
 the paper's two ideal-speedup footnotes (Section 4.2).
 """
 import itertools
+import os
 
 import numpy as np
 import pytest
@@ -206,3 +207,45 @@ def test_tile_counts_config2():
     for a, b in zip(*np.nonzero(cls)):
         acc += int(orc.dense_mask(Ic, Ir, D, a * 128, min(T, a * 128 + 128), b * 128, min(T, b * 128 + 128)).sum())
     assert acc == total
+
+
+# ---- fixtures written out by hand / from the paper's printed formulas (tests/golden)
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+
+
+def _read_matrix(name):
+    rows = [ln.split() for ln in open(os.path.join(GOLDEN, name)) if ln.strip() and not ln.startswith("#")]
+    return np.array(rows, dtype=np.int64).astype(bool)
+
+
+def test_golden_mask_single_sequence():
+    want = _read_matrix("mask_p3_c2_r2.txt")
+    q = np.arange(7)[:, None]
+    kv = np.arange(7)[None, :]
+    assert np.array_equal(orc.prefix_sharing_mask(q, kv, 3, 5), want)
+    Ic, Ir, D = orc.index_arrays([0], [3], [2], [2], 7)
+    assert np.array_equal(orc.dense_mask(Ic, Ir, D), want)
+    assert orc.count_allowed(Ic, Ir, D) == int(want.sum()) == 24  # 6 + 6 + 3 + 6 + 3
+
+
+def test_golden_mask_packed_row_with_padding():
+    want = _read_matrix("mask_packed_two_samples.txt")
+    Ic, Ir, D = orc.index_arrays([0, 4], [2, 1], [1, 1], [1, 1], 8)
+    assert np.array_equal(orc.dense_mask(Ic, Ir, D), want)
+    assert orc.count_allowed(Ic, Ir, D) == int(want.sum())
+
+
+def test_golden_ideal_speedups():
+    for ln in open(os.path.join(GOLDEN, "ideal_speedups.txt")):
+        if not ln.strip() or ln.startswith("#"):
+            continue
+        p, c, lin, quad = ln.split()
+        p, c, lin, quad = int(p), int(c), float(lin), float(quad)
+        # token counts: exact; pair counts: the formula is the limit for long sequences
+        assert (2 * p + 2 * c) / (p + 2 * c) == pytest.approx(lin, rel=1e-9)
+        shared = tri(p) + 2 * (c * p + tri(c))
+        paired = 2 * tri(p + c)
+        assert paired / shared == pytest.approx(quad, rel=4.0 / (p + c))
+        if p + 2 * c <= 1536:  # the oracle's own count, where the dense mask is small
+            Ic, Ir, D = orc.index_arrays([0], [p], [c], [c], p + 2 * c)
+            assert orc.count_allowed(Ic, Ir, D) == shared
