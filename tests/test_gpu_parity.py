@@ -15,7 +15,7 @@ F32_TOL = 1e-5
 BF16_O_TOL, BF16_LSE_TOL, BF16_GRAD_TOL = 1e-2, 1e-3, 2e-2
 
 
-def compare_full(w, tens, out, tol_kind):
+def compare_full(w, tens, out, tol_kind, o_tol_by_magnitude=False):
     Ic, Ir, D = oracle_arrays(w)
     ref = orc.backward(tens["Q"], tens["K"], tens["V"], tens["dO"], w.scale, Ic, Ir, D)
     real = D != orc.PAD_DOC
@@ -29,8 +29,16 @@ def compare_full(w, tens, out, tol_kind):
         err = np.abs(out["LSE"][:, real] - ref["LSE"][:, real]).max() if real.any() else 0.0
         assert err <= F32_TOL, ("LSE", err)
     else:
-        err = np.abs(out["O"] - ref["O"]).max() if out["O"].size else 0.0
-        assert err <= BF16_O_TOL, ("O", err)
+        if o_tol_by_magnitude:
+            # The oracle is fp64, the output bf16: an element of magnitude x cannot be closer than
+            # half a bf16 ulp, x * 2^-8 in the worst case, which alone exceeds the 1e-2 bar from
+            # |x| = 2.56 on.  Such elements (rows with two or three keys and large |V|) get that
+            # rounding on top of 5e-3 for the arithmetic; everything else keeps the 1e-2 bar.
+            allowed = np.maximum(BF16_O_TOL, 5e-3 + np.abs(ref["O"]) * 2.0 ** -8)
+            assert np.all(np.abs(out["O"] - ref["O"]) <= allowed), ("O", float((np.abs(out["O"] - ref["O"]) - allowed).max()))
+        else:
+            err = np.abs(out["O"] - ref["O"]).max() if out["O"].size else 0.0
+            assert err <= BF16_O_TOL, ("O", err)
         err = np.abs(out["LSE"][:, real] - ref["LSE"][:, real]).max() if real.any() else 0.0
         assert err <= BF16_LSE_TOL, ("LSE", err)
         for name in ("dQ", "dK", "dV"):
@@ -204,6 +212,21 @@ def test_bf16_packed_rows_random():
     tens = W.make_tensors(w)
     out, _ = run_gpu(w, tens)
     compare_full(w, tens, out, "bf16")
+
+
+def test_bf16_long_sample_tile_lists_beyond_two_batches():
+    """One sample of 9 200 tokens: tile lists of up to 144 entries, so the kernels' 64-entry
+    list windows are refilled twice (the five configurations stop at 128 entries); two q-heads
+    on one kv-head; the whole sample against the oracle."""
+    w = W.custom_workload([(7200, 1700, 300)], offsets=[17], total_tokens=9250, hq=2, hkv=1, d=128,
+                          dtype="bf16", seed=71)
+    tens = W.make_tensors(w)
+    out, meta = run_gpu(w, tens)
+    rp, _, _ = meta.csr(ps.GRID_FWD)
+    assert np.diff(rp).max() > 128
+    rp, _, _ = meta.csr(ps.GRID_BWD)
+    assert np.diff(rp).max() > 128
+    compare_full(w, tens, out, "bf16", o_tol_by_magnitude=True)
 
 
 def test_bf16_nonpositive_scale_uses_generic_kernels():
