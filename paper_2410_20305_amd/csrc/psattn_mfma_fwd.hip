@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         dma_wait_barrier<0>();
         const int k0 = (ent >> 2) * 64;
         const bool full = (ent & 3) == PSATTN_TILE_FULL;
-        // The next tile's copy is issued piece by piece in the first eight slots below.  After
+        // The next tile's copy is issued piece by piece, on every other slot of the S phase.  After
         // the last tile the same tile is copied once more (to the other buffer, which nobody
         // reads), so the slots need no branch.
         if (it + 1 < n_ent) {
