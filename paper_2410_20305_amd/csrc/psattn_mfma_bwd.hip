@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
         static_for<0, 8>([&](auto P) { pair_copy_piece<decltype(P)::value>(pc, sKb[0], sVb[0], w); });
     }
     const LaneOffsets lo = lane_offsets(l);
-    constexpr int kAhead = 3, kRing = 4;
+    constexpr int kAhead = 2, kRing = 4;  // measured: 1 and 3 are both slower
     // One tile = 48 MFMA slots, per block kb of 32 keys:
     //   slots 24 kb +  0-15  S^T = K Q^T and dP^T = V dO^T (alternating)
     //   (dS arithmetic of the block)

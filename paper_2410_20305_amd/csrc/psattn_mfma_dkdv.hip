@@ -75,7 +75,7 @@ __device__ __forceinline__ void settle() {
 // The LDS operand of slot m is requested kAhead slots earlier into a register ring.
 
 constexpr int kQTileBytes = 64 * kRowBytes;
-constexpr int kAhead = 5;
+constexpr int kAhead = 4;  // measured: 3 and 5 are both slower
 
 // AND-masks for the packed bf16 pairs (elements 2j, 2j + 1 of block b) of one q-tile:
 // the queries allowed to read this lane's key are rows [lo, hi) of the tile.
