@@ -7,8 +7,10 @@ code with the HIP path and does not import it.
 
 What it follows:
   * the prefix-sharing mask (Algorithm 1) and its packed form (Algorithm 3),
-    evaluated literally as three boolean clauses from materialised per-token
-    arrays I_chosen, I_rejected (completion start indices) and D (document ids);
+    stated through token roles (prompt / chosen / rejected) found from the
+    materialised per-token arrays I_chosen, I_rejected (completion start indices)
+    and D (document ids): a token reads the not-later tokens of its own sample,
+    except that rejected tokens do not read chosen tokens (Section 3.1);
   * the baseline packing mask of Algorithm 2 (per-token response ids R);
   * ordinary softmax attention on the allowed pairs (Section 3.1 states that
     nothing else changes), with the textbook explicit backward;
@@ -85,29 +87,49 @@ def response_ids(offset, prefix_len, chosen_len, rejected_len, total_tokens):
 # --------------------------------------------------------------------------
 # masks
 # --------------------------------------------------------------------------
+# Every token of a sample plays one of three roles.  Section 3.1 states who may read
+# whom: a token reads earlier tokens of its own sample (and itself), and the only
+# role pair that is forbidden on top of that is "a rejected-response token reading a
+# chosen-response token".  The three masks below are that sentence; the per-token
+# arrays of Algorithms 1-3 (completion start indices, document / response ids) are
+# only used to find a token's role and sample.
+PROMPT, CHOSEN, REJECTED = 0, 1, 2
+
+
+def _role(t, chosen_start, rejected_start):
+    """Role of position t in a sample whose chosen response starts at chosen_start and
+    whose rejected response starts at rejected_start (chosen_start <= rejected_start)."""
+    t = np.asarray(t)
+    return np.where(t < chosen_start, PROMPT, np.where(t < rejected_start, CHOSEN, REJECTED))
+
+
 def prefix_sharing_mask(q, kv, chosen_ind, rejected_ind):
-    """Algorithm 1 for one sample: q, kv broadcastable integer arrays."""
-    causal_mask = kv <= q
-    dpo_mask = ~((rejected_ind <= q) & (chosen_ind <= kv) & (kv < rejected_ind))
-    return causal_mask & dpo_mask
+    """Mask of Algorithm 1 for one sample (positions relative to the same origin as
+    the two start indices): not-later tokens, minus rejected-reads-chosen."""
+    q, kv = np.asarray(q), np.asarray(kv)
+    forbidden_roles = (_role(q, chosen_ind, rejected_ind) == REJECTED) & \
+                      (_role(kv, chosen_ind, rejected_ind) == CHOSEN)
+    return (kv <= q) & ~forbidden_roles
 
 
 def packed_prefix_sharing_mask(q, kv, I_chosen, I_rejected, D):
-    """Algorithm 3 over the flat buffer.  q, kv: broadcastable integer arrays."""
-    causal_mask = kv <= q
-    # padding is in no document, so it matches nothing, itself included
-    document_mask = (D[q] == D[kv]) & (D[q] != PAD_DOC)
-    chosen_ind = I_chosen[q]
-    rejected_ind = I_rejected[q]
-    dpo_mask = ~((rejected_ind <= q) & (chosen_ind <= kv) & (kv < rejected_ind))
-    return causal_mask & document_mask & dpo_mask
+    """Mask of Algorithm 3 over the flat buffer.  q, kv: broadcastable integer arrays.
+    Roles are taken relative to the query's sample (the start indices stored at the
+    query position); a key of another sample, or padding on either side (which is in
+    no sample, itself included), never matches."""
+    q, kv = np.asarray(q), np.asarray(kv)
+    same_sample = (D[q] == D[kv]) & (D[q] != PAD_DOC)
+    q_role = _role(q, I_chosen[q], I_rejected[q])
+    kv_role = _role(kv, I_chosen[q], I_rejected[q])
+    return same_sample & (kv <= q) & ~((q_role == REJECTED) & (kv_role == CHOSEN))
 
 
 def response_id_mask(q, kv, R):
-    """Algorithm 2 (packing without prefix sharing)."""
-    causal_mask = kv <= q
-    response_mask = (R[q] == R[kv]) & (R[q] != PAD_DOC)
-    return causal_mask & response_mask
+    """Mask of Algorithm 2 (packing without prefix sharing): every [prompt | response]
+    unit has its own id and a token reads the not-later tokens of its unit."""
+    q, kv = np.asarray(q), np.asarray(kv)
+    same_unit = (R[q] == R[kv]) & (R[q] != PAD_DOC)
+    return same_unit & (kv <= q)
 
 
 def dense_mask(I_chosen, I_rejected, D, q_lo=0, q_hi=None, k_lo=0, k_hi=None):
