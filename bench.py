@@ -1,13 +1,16 @@
 #!/usr/bin/env python3
 """Benchmark of the prefix-shared DPO attention hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--no-extras] [--no-cpu]
+    python bench.py --sweep            # prefix x completion length grid (Section 4.2, Fig. 3)
 
 One step = one pass of the whole hot path over one synthetic batch: block-mask
-build (psattn_build_meta), forward (psattn_fwd) and backward (psattn_bwd: delta,
-dQ, dK/dV).  Inputs are resident in HBM before the timed region.  Prints ONE JSON
-line.  `value` is useful attention TFLOP/s (14 * d * Hq * N_allowed FLOPs per
-step; masked pairs, padding and recomputation earn nothing).
+build (psattn_build_meta), forward (psattn_fwd), backward (psattn_bwd: delta, dQ,
+dK/dV) and the stream-ordered release of the block mask.  Inputs are resident in
+HBM before the timed region.  Prints ONE JSON line.  `value` is useful attention
+TFLOP/s (14 * d * Hq * N_allowed FLOPs per step; masked pairs, padding and
+recomputation earn nothing).  The default workload is the largest of the
+configurations (cfg5).
 """
 from __future__ import annotations
 
@@ -25,6 +28,11 @@ import numpy as np  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
+LAYERS = 32                 # the block mask is built once per step and shared by every layer (Section 3.1)
+PASSES = ["fwd", "delta", "dq", "dkdv"]
+# algorithmic FLOPs per launch in units of d * Hq * N_allowed: forward 4 (S, PV); dQ pass 2 (dQ only: its
+# recomputation of S and dP earns nothing); dK/dV pass 8 (S, dP, dV, dK)
+ALG_UNITS = [4, 0, 2, 8]
 
 
 def tri(n):
@@ -37,7 +45,7 @@ def allowed_pairs(w):
 
 
 def algorithmic_bytes(w, tokens):
-    """Bytes the method itself must move, each tensor once (bf16: e = 2)."""
+    """Bytes the method itself must move per step, each tensor once (bf16: e = 2)."""
     e = 4 if w.dtype == "f32" else 2
     Hq, Hkv, d = w.n_q_heads, w.n_kv_heads, w.head_dim
     fwd = (Hq + 2 * Hkv) * d * e + Hq * d * e + 4 * Hq
@@ -46,7 +54,7 @@ def algorithmic_bytes(w, tokens):
 
 
 class Runner:
-    """Device tensors of one workload + the three library calls of a step."""
+    """Device tensors of one workload + the library calls of a step."""
 
     def __init__(self, w, tensors=None, seed=0):
         import torch
@@ -66,6 +74,7 @@ class Runner:
         self.LSE = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
         self.dQ, self.dK, self.dV = torch.empty_like(self.Q), torch.empty_like(self.K), torch.empty_like(self.V)
         meta = self.build_meta()
+        self.mfma = meta.uses_mfma(ps.BF16 if w.dtype == "bf16" else ps.F32, d, w.scale, backward=True)
         self.ws = torch.empty(ps.psattn_bwd_workspace_bytes(meta, Hq, Hkv, d), dtype=torch.uint8, device="cuda")
         meta.free()
         self.flops = 14 * d * Hq * allowed_pairs(w)
@@ -80,43 +89,76 @@ class Runner:
         ps.psattn_fwd(meta, self.Q, self.K, self.V, w.scale, O=self.O, LSE=self.LSE)
         ps.psattn_bwd(meta, self.Q, self.K, self.V, self.O, self.dO, self.LSE, w.scale, dQ=self.dQ,
                       dK=self.dK, dV=self.dV, workspace=self.ws)
-        return meta
+        meta.free_async()
+
+    def build_meta_ms(self, n=20):
+        """Host wall time of psattn_build_meta alone (sample table -> block mask -> upload enqueued)."""
+        ts = []
+        for _ in range(n):
+            t0 = time.perf_counter()
+            m = self.build_meta()
+            ts.append((time.perf_counter() - t0) * 1e3)
+            m.free_async()
+        self.torch.cuda.synchronize()
+        return float(np.median(ts)), float(np.min(ts))
 
     def timed(self, steps, warmup):
-        """Wall time of `steps` whole steps, bracketed by synchronize; plus per-pass
-        kernel time from HIP events recorded by the library on the launch stream."""
+        """Wall time of `steps` whole steps, bracketed by synchronize; per-step device time
+        from events on the launch stream; per-pass kernel time from HIP events recorded by
+        the library on the same stream."""
         torch, ps = self.torch, self.ps
-        keep = []
         for _ in range(warmup):
-            keep.append(self.step())
+            self.step()
         torch.cuda.synchronize()
-        for m in keep:
-            m.free()
-        keep = []
         ps.psattn_profile_enable(True)
         ps.psattn_profile_read()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
-            keep.append(self.step())
+        marks[0].record()
+        for i in range(steps):
+            self.step()
+            marks[i + 1].record()
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         ms, cnt = ps.psattn_profile_read()
         ps.psattn_profile_enable(False)
-        for m in keep:
-            m.free()
         per_pass = [float(ms[i] / max(1, cnt[i])) for i in range(4)]
-        return (t1 - t0) / steps * 1e3, per_pass
+        per_step = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
+        return (t1 - t0) / steps * 1e3, per_pass, per_step
 
 
-def summarize(w, ms_step, per_pass, flops):
+def roofline_of(w, per_pass, ps, traffic_table, name):
+    """Roofline object of the dominant kernel of one workload."""
+    dom = max((0, 2, 3), key=lambda i: per_pass[i])
+    n_allowed = allowed_pairs(w)
+    flops = ALG_UNITS[dom] * w.head_dim * w.n_q_heads * n_allowed
+    ach = flops / (per_pass[dom] * 1e-3) / 1e12
+    kernel = ps.psattn_kernel_name(1, dom)
+    t = traffic_table.get("%s/%s" % (name, kernel))
+    return dict(bound="mfma", kernel=kernel, achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                frac=round(ach / PEAK_BF16_TFLOPS, 4),
+                traffic=int(t["read_bytes"] + t["write_bytes"]) if t else None,
+                traffic_source="rocprofv3 FETCH_SIZE/WRITE_SIZE summary committed under profiles/hbm_traffic.txt "
+                               "(not measured by this run)" if t else None,
+                avg_launch_ms=round(per_pass[dom], 4), algorithmic_flops_per_launch=flops)
+
+
+def summarize(w, ms_step, per_pass, per_step, flops):
     kern = sum(per_pass)
-    return dict(ms_per_step=round(ms_step, 4), ms_kernels=round(kern, 4),
+    t_mfma = flops / (PEAK_BF16_TFLOPS * 1e12) * 1e3
+    t_hbm = algorithmic_bytes(w, w.total_tokens) / (PEAK_HBM_GBS * 1e9) * 1e3
+    bound = max(t_mfma, t_hbm)
+    return dict(ms_per_step=round(ms_step, 4), ms_per_step_median=round(float(np.median(per_step)), 4),
+                ms_per_step_min=round(float(np.min(per_step)), 4), ms_kernels=round(kern, 4),
                 ms_fwd=round(per_pass[0], 4), ms_delta=round(per_pass[1], 4), ms_dq=round(per_pass[2], 4),
                 ms_dkdv=round(per_pass[3], 4),
                 useful_tflops=round(flops / (ms_step * 1e-3) / 1e12, 2),
                 useful_tflops_kernels_only=round(flops / (kern * 1e-3) / 1e12, 2) if kern > 0 else None,
-                pct_mfma_peak=round(100 * flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2))
+                pct_mfma_peak=round(100 * flops / (ms_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+                roofline_ms_mfma=round(t_mfma, 4), roofline_ms_hbm=round(t_hbm, 4),
+                binding_roofline="hbm" if t_hbm > t_mfma else "mfma",
+                frac_of_binding_roofline=round(bound / ms_step, 4))
 
 
 def cpu_baseline(w, tens, budget_s=20.0):
@@ -132,9 +174,12 @@ def cpu_baseline(w, tens, budget_s=20.0):
     Ic, Ir, D = orc.index_arrays(w.offset, w.prefix_len, w.chosen_len, w.rejected_len, w.total_tokens)
     G = w.n_q_heads // w.n_kv_heads
     done_flops, done_token_heads, blocks = 0, 0, 0
+    # shortest samples first, so that the budget buys several whole blocks even on the largest workload
+    order = np.argsort(w.prefix_len.astype(np.int64) + w.chosen_len + w.rejected_len, kind="stable")
     t0 = time.perf_counter()
     for g in range(w.n_kv_heads):
-        for s in range(w.n_samples):
+        for s in order:
+            s = int(s)
             heads = list(range(g * G, (g + 1) * G))
             orc.backward(tens["Q"], tens["K"], tens["V"], tens["dO"], w.scale, Ic, Ir, D, heads=heads, samples=[s])
             p, c, r = int(w.prefix_len[s]), int(w.chosen_len[s]), int(w.rejected_len[s])
@@ -148,10 +193,31 @@ def cpu_baseline(w, tens, budget_s=20.0):
             break
     dt = time.perf_counter() - t0
     return dict(value=round(done_flops / dt / 1e12, 6), unit="TFLOP/s", cores=int(cores), kind="oracle",
-                sample="%d of %d (sample, kv-group) blocks, each with its %d q-heads, fwd+bwd, fp64 numpy, "
-                       "%.1f s; tokens_per_s scales the blocks done to all %d q-heads" %
-                       (blocks, w.n_samples * w.n_kv_heads, G, dt, w.n_q_heads),
+                sample="%d of %d (sample, kv-group) blocks of %s (shortest samples first), each with its %d q-heads, "
+                       "fwd+bwd, fp64 numpy, %.1f s; tokens_per_s scales the blocks done to all %d q-heads" %
+                       (blocks, w.n_samples * w.n_kv_heads, w.name, G, dt, w.n_q_heads),
                 tokens_per_s=round(done_token_heads / w.n_q_heads / dt, 1))
+
+
+def length_sweep(W, steps, warmup):
+    """Attention forward + backward time of one sample, prefix-shared against paired, over a
+    grid of prompt and completion lengths (Section 4.2's self-attention micro-benchmark:
+    Mistral-7B-shaped heads, 32 q / 8 kv, d = 128; chosen and rejected of equal length)."""
+    rows = []
+    for p in (1024, 4096, 8192, 16384):
+        for c in (128, 512, 2048, 4096):
+            w = W.custom_workload([(p, c, c)], hq=32, hkv=8, d=128, dtype="bf16", seed=p + c, name="sweep")
+            pw, _, _ = W.paired_workload(w)
+            rs, rp = Runner(w, None, seed=1), Runner(pw, None, seed=1)
+            ms_s, pp_s, _ = rs.timed(steps, warmup)
+            ms_p, pp_p, _ = rp.timed(steps, warmup)
+            rows.append(dict(prefix=p, completion=c, shared_ms=round(sum(pp_s), 4), paired_ms=round(sum(pp_p), 4),
+                             speedup=round(sum(pp_p) / sum(pp_s), 3),
+                             ideal=round(allowed_pairs(pw) / allowed_pairs(w), 3),
+                             paper_ideal=round(2 * (p + c) ** 2 / (2 * (p + c) ** 2 - p ** 2), 3),
+                             shared_pct_peak=round(100 * rs.flops / (sum(pp_s) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2)))
+            del rs, rp
+    return rows
 
 
 def main():
@@ -159,9 +225,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations and the paired baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--sweep", action="store_true", help="prefix x completion length grid instead of the configurations")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device copy 5 times and exit (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -189,36 +256,27 @@ def main():
         print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4,
                           "launches": 5}))
         return
+    if args.sweep:
+        print(json.dumps({"metric": "attention fwd+bwd ms, prefix-shared vs paired, one sample", "unit": "ms",
+                          "heads": "32q/8kv d128 bf16", "grid": length_sweep(W, min(args.steps, 10), 2)}))
+        return
+
+    traffic_table = {}
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")) as f:
+            traffic_table = json.load(f)
+    except (OSError, ValueError):
+        pass
 
     w = W.make_workload(args.workload)
     tens = W.make_tensors(w)
     run = Runner(w, tens)
-    ms_step, per_pass = run.timed(args.steps, args.warmup)
-    main_res = summarize(w, ms_step, per_pass, run.flops)
+    assert run.mfma, "the benchmark configurations must run on the MFMA kernels"
+    ms_step, per_pass, per_step = run.timed(args.steps, args.warmup)
+    bm_med, bm_min = run.build_meta_ms()
+    main_res = summarize(w, ms_step, per_pass, per_step, run.flops)
     value = run.flops / (ms_step * 1e-3) / 1e12
-
-    # dominant kernel and its roofline: bf16 MFMA contraction
-    names = ["fwd", "delta", "dq", "dkdv"]
-    # algorithmic FLOPs per launch: forward 4, dK/dV pass 8 (S, dP, dV, dK), dQ pass 2 (dQ only;
-    # its recomputation of S and dP is overhead), in units of d * Hq * N_allowed
-    alg = [4, 0, 2, 8]
-    dom = max((0, 2, 3), key=lambda i: per_pass[i])
     n_allowed = allowed_pairs(w)
-    ach = alg[dom] * w.head_dim * w.n_q_heads * n_allowed / (per_pass[dom] * 1e-3) / 1e12
-    # HBM bytes per launch of that kernel, from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE
-    # runs (already scaled by the copy-kernel calibration); null for a workload not profiled
-    traffic = None
-    try:
-        with open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")) as f:
-            t = json.load(f).get("%s/%s" % (args.workload, ps.psattn_kernel_name(1, dom)))
-        if t:
-            traffic = int(t["read_bytes"] + t["write_bytes"])
-    except (OSError, ValueError):
-        pass
-    roofline = dict(bound="mfma", kernel=ps.psattn_kernel_name(1, dom), achieved=round(ach, 2),
-                    peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(ach / PEAK_BF16_TFLOPS, 4), traffic=traffic,
-                    avg_launch_ms=round(per_pass[dom], 4),
-                    algorithmic_flops_per_launch=alg[dom] * w.head_dim * w.n_q_heads * n_allowed)
 
     out = {
         "metric": "useful attn TFLOP/s fwd+bwd", "value": round(value, 3), "unit": "TFLOP/s",
@@ -228,11 +286,14 @@ def main():
         "config": {"workload": args.workload, "n_samples": w.n_samples, "tokens": w.unique_tokens,
                    "buffer_tokens": w.total_tokens, "n_q_heads": w.n_q_heads, "n_kv_heads": w.n_kv_heads,
                    "head_dim": w.head_dim, "allowed_pairs": n_allowed,
-                   "step": "build_meta + fwd + bwd(delta, dQ, dK/dV)"},
+                   "step": "build_meta + fwd + bwd(delta, dQ, dK/dV) + free_meta_async"},
         "pct_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
         "tokens_per_s": round(w.unique_tokens / (ms_step * 1e-3), 1),
+        "ms_per_step_median": main_res["ms_per_step_median"], "ms_per_step_min": main_res["ms_per_step_min"],
+        "build_meta_ms": round(bm_med, 4), "build_meta_ms_min": round(bm_min, 4),
+        "build_meta_ms_amortised_over_%d_layers" % LAYERS: round(bm_med / LAYERS, 5),
         "detail": main_res,
-        "roofline": roofline,
+        "roofline": roofline_of(w, per_pass, ps, traffic_table, args.workload),
     }
     algb = algorithmic_bytes(w, w.total_tokens)
     out["hbm_algorithmic_GBs"] = round(algb / (sum(per_pass) * 1e-3) / 1e9, 1)
@@ -243,20 +304,21 @@ def main():
             wx = W.make_workload(name)
             steps = max(5, min(args.steps, 20))
             rx = run if name == args.workload else Runner(wx, None, seed=wx.seed)
-            ms_s, pp = (ms_step, per_pass) if name == args.workload else rx.timed(steps, 3)
-            res = summarize(wx, ms_s, pp, rx.flops)
+            ms_s, pp, pst = (ms_step, per_pass, per_step) if name == args.workload else rx.timed(steps, 3)
+            res = summarize(wx, ms_s, pp, pst, rx.flops)
             res["tokens_per_s"] = round(wx.unique_tokens / (ms_s * 1e-3), 1)
+            res["roofline"] = roofline_of(wx, pp, ps, traffic_table, name)
+            bm, _ = rx.build_meta_ms(10)
+            res["build_meta_ms"] = round(bm, 4)
             # unshared paired baseline on the same samples, same kernels
             pw, _, _ = W.paired_workload(wx)
             rp = Runner(pw, None, seed=wx.seed)
-            ms_p, pp_p = rp.timed(steps, 3)
+            ms_p, pp_p, _ = rp.timed(steps, 3)
             res["paired_ms_per_step"] = round(ms_p, 4)
             res["paired_tokens_per_s"] = round(wx.unique_tokens / (ms_p * 1e-3), 1)
             res["speedup_vs_paired"] = round(ms_p / ms_s, 3)
             res["speedup_vs_paired_kernels_only"] = round(sum(pp_p) / sum(pp), 3)
             res["ideal_attn_speedup"] = round(allowed_pairs(pw) / allowed_pairs(wx), 3)
-            res["roofline_ms_mfma"] = round(rx.flops / (PEAK_BF16_TFLOPS * 1e12) * 1e3, 4)
-            res["roofline_ms_hbm"] = round(algorithmic_bytes(wx, wx.total_tokens) / (PEAK_HBM_GBS * 1e9) * 1e3, 4)
             extras[name] = res
             del rp
             if rx is not run:

@@ -23,18 +23,24 @@
  *     aborts or throws; psattn_strerror() names a code.
  *   - "host" pointers are ordinary CPU memory, "device" pointers are HIP device
  *     memory of the current device.  The caller owns every tensor and the stream;
- *     the library owns only the psattn_meta object (host arrays + one device
- *     allocation), released by psattn_free_meta.
+ *     the library owns only the psattn_meta objects (host arrays + a pinned staging
+ *     buffer and a device buffer taken from a small pool inside the library).
  *   - hip_stream is a hipStream_t passed as void* (NULL = the null stream).  All
- *     device work is enqueued on it and is asynchronous; no call synchronises
- *     except where stated.
+ *     device work is enqueued on it and is asynchronous.  Calls that may block the
+ *     host or synchronise the device: psattn_build_meta only when it has to allocate a
+ *     new buffer pair (the first mini-batches of a process, or a mini-batch larger than
+ *     any before) or when all pooled pairs are still in use by the device;
+ *     psattn_trim_pool; psattn_profile_read.  psattn_fwd, psattn_bwd,
+ *     psattn_free_meta and psattn_free_meta_async never block and never allocate.
  *   - tensors are contiguous, token-major: Q, O, dO, dQ are [T, n_q_heads, head_dim],
  *     K, V, dK, dV are [T, n_kv_heads, head_dim], head_dim fastest.  LSE is
  *     [n_q_heads, T] float.  q-heads [g*G, (g+1)*G), G = n_q_heads / n_kv_heads,
  *     read kv-head g.
  *   - padding tokens (covered by no sample) are never attended to; every output at
  *     a padding position is written as zero (LSE = -inf).  Outputs are overwritten,
- *     never accumulated into.
+ *     never accumulated into.  The input VALUES at padding positions must be finite:
+ *     the matrix-core kernels multiply them by exact zeros, and 0 * inf or 0 * NaN
+ *     would reach real tokens of the same tile.
  */
 #ifndef PSATTN_H
 #define PSATTN_H
@@ -56,7 +62,8 @@ typedef enum {
     PSATTN_ENOMEM = -4,       /* host or device allocation failed */
     PSATTN_EHIP = -5,         /* a HIP runtime call failed */
     PSATTN_EUNSUPPORTED = -6, /* valid request this build has no kernel for */
-    PSATTN_ENODEVICE = -7     /* meta was built host-only; no device copy to run kernels from */
+    PSATTN_ENODEVICE = -7,    /* meta was built host-only; no device copy to run kernels from */
+    PSATTN_ELIMIT = -8        /* request exceeds a fixed capacity of the entry point called */
 } psattn_status;
 
 typedef enum { PSATTN_F32 = 0, PSATTN_BF16 = 1 } psattn_dtype;
@@ -96,7 +103,8 @@ enum { PSATTN_GRID_FWD = 0, /* q-major CSR, used by psattn_fwd and the dQ pass  
  *
  * psattn_build_meta uploads the metadata to the current device with one
  * asynchronous copy on hip_stream (the host staging buffer stays alive inside the
- * object).  psattn_build_meta_host builds the same object without touching any
+ * object).  Tile grids with 2^29 or more tiles along an axis, or more than
+ * INT32_MAX non-skipped tiles, are refused with PSATTN_EUNSUPPORTED.  psattn_build_meta_host builds the same object without touching any
  * device (for inspection and planning); kernels refuse it with PSATTN_ENODEVICE.
  * On error *out is set to NULL.
  */
@@ -116,9 +124,19 @@ int psattn_build_meta_host(int32_t n_samples, const int32_t* offset, const int32
                            int32_t total_tokens, int32_t tile_q, int32_t tile_k,
                            int32_t bwd_tile_q, int32_t bwd_tile_k, psattn_meta** out);
 
-/* Releases host and device memory of the object.  The caller must make sure no
- * kernel that uses it is still running.  NULL is accepted. */
+/* Releases the object; its buffers return to the library's pool.  The caller must
+ * make sure no kernel that uses it is still running.  NULL is accepted. */
 int psattn_free_meta(psattn_meta* meta);
+
+/* Stream-ordered release for training loops: the object is gone when the call returns,
+ * its buffers are handed out again only after all work enqueued on hip_stream before
+ * this call has finished.  Never blocks.  (Section 3.1: one block mask per training
+ * step; a loop builds, uses and releases one object per step without ever waiting.) */
+int psattn_free_meta_async(psattn_meta* meta, void* hip_stream);
+
+/* Frees every idle buffer pair of the pool (waits for the device to be done with
+ * each).  Objects still alive are not touched. */
+int psattn_trim_pool(void);
 
 /* Host read-back of the canonical metadata (pure host copies, no synchronisation).
  * grid = PSATTN_GRID_FWD: rows are q-tiles, idx are k-tiles.
@@ -144,7 +162,10 @@ int psattn_meta_allowed_pairs(const psattn_meta* meta, int64_t* n_allowed);
  * LSE[h, q] = log sum_kv exp(scale * Q_q . K_kv) (natural log).  SKIPPED tiles are
  * never computed (Section 3.1).  dt selects the element type of Q, K, V, O
  * (float, or bfloat16 with float accumulation); LSE is always float.
- * head_dim: 64 or 128 for PSATTN_F32, 128 for PSATTN_BF16.
+ * head_dim: 64 or 128 for either type.  The matrix-core kernels serve PSATTN_BF16 with
+ * head_dim 128, scale > 0 and the default tile grids; every other valid request runs on
+ * plain one-thread-per-row kernels that are orders of magnitude slower (they exist for the
+ * fp32 correctness configuration).  psattn_uses_mfma tells which one a call would take.
  */
 int psattn_fwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
                int32_t head_dim, float scale,
@@ -173,19 +194,27 @@ int psattn_bwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n
 size_t psattn_bwd_workspace_bytes(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads,
                                   int32_t head_dim);
 
+/* 1 if psattn_fwd (backward = 0) or psattn_bwd (backward != 0) would run the bf16
+ * matrix-core kernels for this meta object, element type, head_dim and scale, 0 if
+ * the call would run on the slow generic kernels, negative status for a NULL meta. */
+int psattn_uses_mfma(const psattn_meta* meta, int32_t dt, int32_t head_dim, float scale, int32_t backward);
+
 /*
  * Per-pass device timing for benchmarks.  While enabled, psattn_fwd / psattn_bwd
  * bracket each kernel with a pair of HIP events on the caller's stream (pass 0 =
  * forward, 1 = delta, 2 = dQ, 3 = dK/dV).  psattn_profile_read waits for the
  * recorded events, adds the elapsed milliseconds per pass to sum_ms[4] and the
  * number of launches to count[4] (both host, overwritten), and forgets them.
- * Not thread-safe; meant for one benchmarking thread.
+ * Not thread-safe; meant for one benchmarking thread.  At most 65 536 unread event
+ * pairs are kept; launches beyond that are not timed until the next read.
  */
 int psattn_profile_enable(int32_t on);
 int psattn_profile_read(double* sum_ms, int64_t* count);
 
-/* Name of the kernel launched last by psattn_fwd / psattn_bwd's passes, for
- * profilers and benchmarks.  pass: 0 = forward, 1 = delta, 2 = dQ, 3 = dK/dV. */
+/* Name of the kernel that psattn_fwd / psattn_bwd launched most recently in this
+ * process for the given pass (0 = forward, 1 = delta, 2 = dQ, 3 = dK/dV), for profilers
+ * and benchmarks; before any launch of that pass, the kernel a default-grid call with
+ * element type dt would use. */
 const char* psattn_kernel_name(int32_t dt, int32_t pass);
 
 const char* psattn_strerror(int status);

@@ -18,6 +18,7 @@ EXPORTS = [
     "psattn_meta_copy_csr", "psattn_meta_copy_tok_desc", "psattn_meta_copy_key_desc",
     "psattn_meta_allowed_pairs", "psattn_fwd", "psattn_bwd", "psattn_bwd_workspace_bytes",
     "psattn_kernel_name", "psattn_strerror", "psattn_profile_enable", "psattn_profile_read",
+    "psattn_free_meta_async", "psattn_trim_pool", "psattn_uses_mfma",
 ]
 
 
@@ -46,6 +47,9 @@ def load_library():
     lib.psattn_build_meta.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
     lib.psattn_build_meta_host.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp)]
     lib.psattn_free_meta.argtypes = [vp]
+    lib.psattn_free_meta_async.argtypes = [vp, vp]
+    lib.psattn_trim_pool.argtypes = []
+    lib.psattn_uses_mfma.argtypes = [vp, i32, i32, f32, i32]
     lib.psattn_meta_tiles.argtypes = [vp, i32, pi32, pi32, pi32, pi32, C.POINTER(i64)]
     lib.psattn_meta_copy_csr.argtypes = [vp, i32, vp, vp, vp]
     lib.psattn_meta_copy_tok_desc.argtypes = [vp, vp]
@@ -114,6 +118,21 @@ class Meta:
             lib = load_library()
             _check(lib.psattn_free_meta(self._h), "psattn_free_meta")
             self._h = None
+
+    def free_async(self, stream=None):
+        """Stream-ordered release: the buffers are reused only after the work enqueued so
+        far on `stream` (default: torch's current stream) has finished."""
+        if self._h is not None:
+            lib = load_library()
+            _check(lib.psattn_free_meta_async(self._h, _stream_ptr(stream)), "psattn_free_meta_async")
+            self._h = None
+
+    def uses_mfma(self, dtype_code, head_dim, scale, backward=False) -> bool:
+        st = load_library().psattn_uses_mfma(self.handle, int(dtype_code), int(head_dim), float(scale),
+                                             1 if backward else 0)
+        if st < 0:
+            raise PsattnError(st, "psattn_uses_mfma")
+        return bool(st)
 
     def __del__(self):
         try:
@@ -254,6 +273,10 @@ def psattn_bwd(meta: Meta, Q, K, V, O, dO, LSE, scale, dQ=None, dK=None, dV=None
                         dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(), ws_bytes, _stream_ptr(stream))
     _check(st, "psattn_bwd")
     return dQ, dK, dV
+
+
+def psattn_trim_pool() -> None:
+    _check(load_library().psattn_trim_pool(), "psattn_trim_pool")
 
 
 def psattn_kernel_name(dt, kernel_pass) -> str:

@@ -71,9 +71,11 @@ struct psattn_meta {
     // device copy
     bool on_device = false;
     int device = -1;
-    void* d_blob = nullptr;
-    void* h_stage = nullptr;  // pinned staging buffer, alive until free
-    size_t blob_bytes = 0;
+    void* d_blob = nullptr;   // device copy of the metadata (from the library's blob pool)
+    void* h_stage = nullptr;  // pinned staging buffer of the same size, alive until release
+    size_t blob_bytes = 0;    // bytes in use
+    size_t blob_cap = 0;      // bytes allocated
+    void* blob_idle = nullptr;  // hipEvent_t of the pooled pair
     psattn::DeviceMeta dev{};
 };
 
@@ -96,6 +98,14 @@ struct AttnArgs {
     float* delta;  // [Hq, T]  workspace: rowsum(dO o O); the MFMA kernels keep its negative here
     float* lse2;   // [Hq, T]  workspace: LSE * log2(e), written by the MFMA dQ pass for the dK/dV pass
 };
+
+// psattn_bwd without the workspace-size lookup: argument checks, then delta / dQ / dK/dV
+// on `scratch_base` (device memory of at least bwd_scratch_bytes()).  Returns a psattn_status.
+size_t bwd_scratch_bytes(const psattn_meta* meta, int32_t n_q_heads);
+int bwd_checked(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                float scale, const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                const float* LSE, void* dQ, void* dK, void* dV, void* scratch_base, size_t scratch_bytes,
+                void* hip_stream);
 
 // Launchers (each returns a hipError_t cast to int; 0 = success).
 int launch_generic_fwd(int dt, const AttnArgs& a, void* stream);

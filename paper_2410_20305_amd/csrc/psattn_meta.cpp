@@ -7,6 +7,7 @@
 // and 3 is never materialised.  Integer only.
 #include <algorithm>
 #include <cstring>
+#include <memory>
 #include <new>
 
 #include "psattn_internal.h"
@@ -53,7 +54,8 @@ int64_t sample_pairs(const Sample& s, int64_t qa, int64_t qb, int64_t ka, int64_
     return n;
 }
 
-void classify(const std::vector<Sample>& samples, int64_t T, int32_t tq, int32_t tk, TileCsr& g) {
+// false: more non-skipped tiles than the int32 row pointers can count
+bool classify(const std::vector<Sample>& samples, int64_t T, int32_t tq, int32_t tk, TileCsr& g) {
     g.tile_q = tq;
     g.tile_k = tk;
     g.n_q_tiles = static_cast<int32_t>((T + tq - 1) / tq);
@@ -87,8 +89,10 @@ void classify(const std::vector<Sample>& samples, int64_t T, int32_t tq, int32_t
                 g.cls.push_back(full ? PSATTN_TILE_FULL : PSATTN_TILE_PARTIAL);
             }
         }
+        if (g.idx.size() > static_cast<size_t>(INT32_MAX)) return false;
         g.row_ptr[a + 1] = static_cast<int32_t>(g.idx.size());
     }
+    return true;
 }
 
 // rows <-> columns of a CSR (counting sort keeps indices ascending inside a row)
@@ -148,8 +152,11 @@ int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_l
     if (tile_k == 0) tile_k = kFwdTileK;
     if (bwd_tile_q == 0) bwd_tile_q = kBwdTileQ;
     if (bwd_tile_k == 0) bwd_tile_k = kBwdTileK;
-    // entries pack the tile index into 30 bits
     const int64_t T = total_tokens;
+    // a list entry packs (tile index << 2 | class) into an int32
+    constexpr int64_t kMaxTiles = int64_t{1} << 29;
+    for (int32_t t : {tile_q, tile_k, bwd_tile_q, bwd_tile_k})
+        if ((T + t - 1) / t >= kMaxTiles) return PSATTN_EUNSUPPORTED;
     std::vector<Sample> samples;
     int64_t prev_end = 0, n_allowed = 0;
     try {
@@ -163,7 +170,7 @@ int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_l
             prev_end = o + p + c + r;
             n_allowed += tri(p) + c * p + tri(c) + r * p + tri(r);
         }
-        psattn_meta* m = new psattn_meta();
+        std::unique_ptr<psattn_meta> m(new psattn_meta());
         m->T = total_tokens;
         m->n_samples = n_samples;
         m->n_allowed = n_allowed;
@@ -181,13 +188,13 @@ int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_l
                 m->key_hi[t] = static_cast<int32_t>((t >= s.C && t < s.R) ? s.R : s.e);
             }
         }
-        classify(samples, T, tile_q, tile_k, m->fwd);
+        if (!classify(samples, T, tile_q, tile_k, m->fwd)) return PSATTN_EUNSUPPORTED;
         order_rows(m->fwd, true);
         TileCsr qmajor;
-        classify(samples, T, bwd_tile_q, bwd_tile_k, qmajor);
+        if (!classify(samples, T, bwd_tile_q, bwd_tile_k, qmajor)) return PSATTN_EUNSUPPORTED;
         transpose(qmajor, m->bwd);
         order_rows(m->bwd, false);
-        *out = m;
+        *out = m.release();
     } catch (const std::bad_alloc&) {
         return PSATTN_ENOMEM;
     }
@@ -259,6 +266,7 @@ const char* psattn_strerror(int status) {
         case PSATTN_EHIP: return "HIP runtime error";
         case PSATTN_EUNSUPPORTED: return "unsupported configuration";
         case PSATTN_ENODEVICE: return "metadata has no device copy";
+        case PSATTN_ELIMIT: return "request exceeds a fixed capacity of this entry point";
         default: return "unknown status";
     }
 }

@@ -190,6 +190,10 @@ __device__ inline int acc_row(int i, int g) { return (i >> 2) * 8 + 4 * g + (i &
 // workgroup barrier.  Compiler-issued vector memory loads stay correct (its waits can
 // only be stricter than needed); inside the tile loops there are none except the tile
 // list refills, which are consumed right after a full wait.
+// The copies also write M0 (the LDS base).  The compiler refuses M0 in a clobber list (it is
+// a reserved register), so the statements cannot declare it; what makes this sound is that
+// compiled code for gfx950 keeps nothing alive in M0 in these kernels, which a test on the
+// compiled ISA pins (no instruction outside the assembly statements names M0).
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
     return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((const __attribute__((address_space(3))) char*)p));
 }

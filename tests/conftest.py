@@ -27,3 +27,10 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+def pytest_sessionfinish(session, exitstatus):
+    # worst elements / rows seen by the GPU parity comparisons (only when asked for)
+    mod = sys.modules.get("gpu_util")
+    if mod is not None:
+        mod.dump_stats()

@@ -1,21 +1,22 @@
 """GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same
 seeded inputs.  Tolerances: fp32 max-abs <= 1e-5 on every output; bf16 O max-abs
-<= 1e-2, LSE max-abs <= 1e-3, dQ/dK/dV relative L2 <= 2e-2 per tensor."""
+<= max(1e-2, half a bf16 ulp of the reference + 5e-3) (exactly 1e-2 below |O| = 2),
+LSE max-abs <= 1e-3, dQ/dK/dV relative L2 <= 2e-2 per tensor and, per (token, head) row,
+error norm <= 2e-2 * (the row's norm + the tensor's RMS row norm)."""
 import numpy as np
 import pytest
 
 import paper_2410_20305_amd as ps
 import psattn_workloads as W
 from oracle import psattn_oracle as orc
-from gpu_util import check_padding_zero, oracle_arrays, rel_l2, run_gpu
+from gpu_util import (BF16_GRAD_TOL, BF16_LSE_TOL, BF16_O_TOL, F32_TOL, check_grad, check_o, check_padding_zero,
+                      dq_delta_floor, oracle_arrays, rel_l2, run_gpu)
 
 pytestmark = pytest.mark.gpu
 
-F32_TOL = 1e-5
-BF16_O_TOL, BF16_LSE_TOL, BF16_GRAD_TOL = 1e-2, 1e-3, 2e-2
 
-
-def compare_full(w, tens, out, tol_kind, o_tol_by_magnitude=False):
+def compare_full(w, tens, out, tol_kind, what=None):
+    what = what or w.name
     Ic, Ir, D = oracle_arrays(w)
     ref = orc.backward(tens["Q"], tens["K"], tens["V"], tens["dO"], w.scale, Ic, Ir, D)
     real = D != orc.PAD_DOC
@@ -29,21 +30,12 @@ def compare_full(w, tens, out, tol_kind, o_tol_by_magnitude=False):
         err = np.abs(out["LSE"][:, real] - ref["LSE"][:, real]).max() if real.any() else 0.0
         assert err <= F32_TOL, ("LSE", err)
     else:
-        if o_tol_by_magnitude:
-            # The oracle is fp64, the output bf16: an element of magnitude x cannot be closer than
-            # half a bf16 ulp, x * 2^-8 in the worst case, which alone exceeds the 1e-2 bar from
-            # |x| = 2.56 on.  Such elements (rows with two or three keys and large |V|) get that
-            # rounding on top of 5e-3 for the arithmetic; everything else keeps the 1e-2 bar.
-            allowed = np.maximum(BF16_O_TOL, 5e-3 + np.abs(ref["O"]) * 2.0 ** -8)
-            assert np.all(np.abs(out["O"] - ref["O"]) <= allowed), ("O", float((np.abs(out["O"] - ref["O"]) - allowed).max()))
-        else:
-            err = np.abs(out["O"] - ref["O"]).max() if out["O"].size else 0.0
-            assert err <= BF16_O_TOL, ("O", err)
+        check_o(out["O"], ref["O"], what)
         err = np.abs(out["LSE"][:, real] - ref["LSE"][:, real]).max() if real.any() else 0.0
         assert err <= BF16_LSE_TOL, ("LSE", err)
-        for name in ("dQ", "dK", "dV"):
-            e = rel_l2(out[name], ref[name])
-            assert e <= BF16_GRAD_TOL, (name, e)
+        check_grad(out["dQ"], ref["dQ"], "dQ", what, dq_delta_floor(tens["dO"], ref["O"], tens["K"], w.scale))
+        for name in ("dK", "dV"):
+            check_grad(out[name], ref[name], name, what)
     return ref
 
 
@@ -144,21 +136,20 @@ def compare_subset(w, tens, out, samples, kv_heads, n_rows=64, seed=0):
             o = int(w.offset[s])
             n = int(w.prefix_len[s] + w.chosen_len[s] + w.rejected_len[s])
             sl = slice(o, o + n)
-            err = np.abs(out["O"][sl][:, heads] - ref["O"][sl][:, heads]).max()
-            assert err <= BF16_O_TOL, ("O", s, g, err)
+            what = "%s sample %d kv-group %d" % (w.name, s, g)
+            check_o(out["O"][sl][:, heads], ref["O"][sl][:, heads], what, tok0=o)
             err = np.abs(out["LSE"][heads][:, sl] - ref["LSE"][heads][:, sl]).max()
             assert err <= BF16_LSE_TOL, ("LSE", s, g, err)
-            e = rel_l2(out["dQ"][sl][:, heads], ref["dQ"][sl][:, heads])
-            assert e <= BF16_GRAD_TOL, ("dQ", s, g, e)
+            check_grad(out["dQ"][sl][:, heads], ref["dQ"][sl][:, heads], "dQ", what,
+                       dq_delta_floor(tens["dO"][sl][:, heads], ref["O"][sl][:, heads], tens["K"][sl][:, g], w.scale))
             for name in ("dK", "dV"):
-                e = rel_l2(out[name][sl][:, g], ref[name][sl][:, g])
-                assert e <= BF16_GRAD_TOL, (name, s, g, e)
+                check_grad(out[name][sl][:, g:g + 1], ref[name][sl][:, g:g + 1], name, what)
     rng = np.random.default_rng(seed)
     real = np.nonzero(D != orc.PAD_DOC)[0]
     for h in rng.choice(w.n_q_heads, size=4, replace=False):
         rows = rng.choice(real, size=n_rows // 4, replace=False)
         Or, Lr = orc.forward_rows(tens["Q"], tens["K"], tens["V"], w.scale, Ic, Ir, D, int(h), rows.tolist())
-        assert np.abs(out["O"][rows, h] - Or).max() <= BF16_O_TOL
+        check_o(out["O"][rows, h], Or, "%s rows of head %d" % (w.name, int(h)))
         assert np.abs(out["LSE"][h, rows] - Lr).max() <= BF16_LSE_TOL
 
 
@@ -166,7 +157,7 @@ def test_config3_sampled():
     w = W.make_workload("cfg3")
     tens = W.make_tensors(w)
     out, _ = run_gpu(w, tens)
-    compare_subset(w, tens, out, samples=[0, 9], kv_heads=[5])
+    compare_subset(w, tens, out, samples=[0, 5, 9, 15], kv_heads=[2, 5])
 
 
 def test_config4_sampled():
@@ -177,11 +168,62 @@ def test_config4_sampled():
     compare_subset(w, tens, out, samples=[0, 1, 17, 18, 19, 70, 141, 142], kv_heads=[0, 7])
 
 
-def test_config5_sampled():
+@pytest.mark.parametrize("kv_group", [0, 7])
+def test_config5_sampled(kv_group):
     w = W.make_workload("cfg5")
     tens = W.make_tensors(w)
     out, _ = run_gpu(w, tens)
-    compare_subset(w, tens, out, samples=[4], kv_heads=[3], n_rows=32)
+    # rows hold 2, 3, 3, 2 samples: the first and the last sample of the second row, for the
+    # first and the last kv-group (all 8 q-heads of each)
+    compare_subset(w, tens, out, samples=[2, 4], kv_heads=[kv_group], n_rows=32, seed=kv_group)
+
+
+PAIRED_CASES = {
+    # shared-format sample tables; each is re-laid as plain-causal documents [p|c], [p|r]
+    "two_samples_padding": dict(samples=[(150, 40, 70), (30, 90, 10)], offsets=[5, 300], T=450, hq=4, hkv=2, row_len=0),
+    "multi_tile": dict(samples=[(700, 150, 260), (300, 129, 65), (64, 64, 64)], offsets=None, T=None, hq=4, hkv=1, row_len=0),
+    # packed rows of 1024 tokens with padding tails (units of 2p+c+r are re-packed)
+    "packed_rows": dict(samples=[(200, 60, 90), (120, 30, 150), (90, 200, 40), (310, 20, 25)],
+                        offsets=[0, 350, 1024, 1354], T=2048, hq=4, hkv=2, row_len=1024),
+}
+
+
+@pytest.mark.parametrize("case", sorted(PAIRED_CASES))
+def test_bf16_paired_format(case):
+    """The unshared paired format (Section 2.1; the response-id mask of Algorithm 2): every
+    sample as two plain-causal documents [prompt|chosen], [prompt|rejected], several 128-token
+    tiles long.  Checked against the oracle on the paired buffer, and against the GPU's own
+    prefix-shared result through the token map: outputs of response tokens agree, the two
+    prompt copies' dK/dV add up to the shared prompt's (the no-contamination invariant)."""
+    c = PAIRED_CASES[case]
+    w = W.custom_workload(c["samples"], offsets=c["offsets"], total_tokens=c["T"], hq=c["hq"], hkv=c["hkv"],
+                          d=128, dtype="bf16", seed=23)
+    w.row_len = c["row_len"]
+    tens = W.make_tensors(w)
+    pw, src, dup = W.paired_workload(w)
+    assert int(pw.chosen_len.sum()) == 0 and int(pw.rejected_len.sum()) == 0
+    # paired tensors: copies of the shared rows; dO of the second prompt copy is zero, padding is noise
+    rng = np.random.default_rng(5)
+    ptens = {}
+    for n in ("Q", "K", "V", "dO"):
+        x = W.bf16_round(rng.standard_normal((pw.total_tokens,) + tens[n].shape[1:], dtype=np.float32))
+        x[src >= 0] = tens[n][src[src >= 0]]
+        ptens[n] = x
+    ptens["dO"][dup] = 0.0
+    pout, meta = run_gpu(pw, ptens)
+    assert meta.uses_mfma(ps.BF16, 128, pw.scale, backward=True)
+    compare_full(pw, ptens, pout, "bf16", what="paired " + case)
+    # against the shared format on the GPU
+    out, _ = run_gpu(w, tens)
+    real = src >= 0
+    first = real & ~dup
+    assert np.abs(pout["O"][first] - out["O"][src[first]]).max() <= 2 * BF16_O_TOL
+    assert np.abs(pout["LSE"][:, first] - out["LSE"][:, src[first]]).max() <= 2 * BF16_LSE_TOL
+    assert rel_l2(pout["dQ"][first], out["dQ"][src[first]]) <= 2 * BF16_GRAD_TOL
+    for name in ("dK", "dV"):
+        summed = np.zeros_like(out[name])
+        np.add.at(summed, src[real], pout[name][real])
+        assert rel_l2(summed, out[name]) <= 2 * BF16_GRAD_TOL, name
 
 
 @pytest.mark.parametrize("hq,hkv", [(1, 1), (3, 1), (6, 2), (16, 2)])
@@ -226,7 +268,7 @@ def test_bf16_long_sample_tile_lists_beyond_two_batches():
     assert np.diff(rp).max() > 128
     rp, _, _ = meta.csr(ps.GRID_BWD)
     assert np.diff(rp).max() > 128
-    compare_full(w, tens, out, "bf16", o_tol_by_magnitude=True)
+    compare_full(w, tens, out, "bf16", what="long sample 9200")
 
 
 def test_bf16_nonpositive_scale_uses_generic_kernels():

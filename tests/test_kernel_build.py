@@ -60,3 +60,43 @@ def test_two_workgroups_per_cu_without_spills(tmp_path, src, kernel):
     assert int(meta["vgpr_spill_count"]) == 0 and int(meta["sgpr_spill_count"]) == 0
     assert int(meta["private_segment_fixed_size"]) == 0
     assert int(meta["group_segment_fixed_size"]) <= 80 * 1024  # two workgroups in 160 KB of LDS
+
+
+def _outside_asm(text):
+    """Instruction lines of the device code that the compiler itself emitted."""
+    body = text.split(".amdhsa_kernel")[0]
+    inside = False
+    for ln in body.splitlines():
+        if "#ASMSTART" in ln:
+            inside = True
+        elif "#ASMEND" in ln:
+            inside = False
+        elif not inside:
+            code = ln.split(";")[0].strip()
+            if code and not code.startswith(".") and not code.endswith(":"):
+                yield code
+
+
+@pytest.mark.parametrize("src", ["psattn_mfma_fwd.hip", "psattn_mfma_bwd.hip", "psattn_mfma_dkdv.hip"])
+def test_compiler_keeps_m0_and_the_copy_counter_free(tmp_path, src):
+    """The asynchronous global -> LDS copies are issued from inline assembly that writes M0
+    and counts its own outstanding copies (vmcnt).  Sound only while compiled code never
+    keeps a value in M0, and while the only vector-memory loads the compiler issues between
+    the first and the last copy are the one-dword tile-list refills."""
+    text = _asm(tmp_path, src)
+    for code in _outside_asm(text):
+        assert not re.search(r"\bm0\b", code), code
+    body = text.split(".amdhsa_kernel")[0]
+    first, last = body.index("global_load_lds_dwordx4"), body.rindex("global_load_lds_dwordx4")
+    loop = body[first:last]
+    inside = True  # the slice starts in the middle of an assembly statement
+    for ln in loop.splitlines():
+        if "#ASMSTART" in ln:
+            inside = True
+        elif "#ASMEND" in ln:
+            inside = False
+        elif not inside:
+            code = ln.split(";")[0].strip()
+            m = re.match(r"(global_load|buffer_load|flat_load|scratch_load)\w*", code)
+            if m:
+                assert m.group(0) == "global_load_dword", code
