@@ -194,6 +194,22 @@ int psattn_bwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n
 size_t psattn_bwd_workspace_bytes(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads,
                                   int32_t head_dim);
 
+/*
+ * psattn_bwd without a workspace argument, for callers that cannot allocate device
+ * memory: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  The scratch lives in a 32 MiB device array inside the library (one copy
+ * per device, held until the process ends); the call allocates nothing.  Limit:
+ * n_q_heads * T <= psattn_bwd_static_max_rows() (4 194 304), otherwise PSATTN_ELIMIT and
+ * nothing is launched.  All calls on one device share that array: calls that overlap on
+ * one device (different streams or threads) race; calls on one stream are safe.
+ * Everything else is as for psattn_bwd.
+ */
+int psattn_bwd_static(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
+                      int32_t head_dim, float scale,
+                      const void* Q, const void* K, const void* V, const void* O, const void* dO,
+                      const float* LSE, void* dQ, void* dK, void* dV, void* hip_stream);
+size_t psattn_bwd_static_max_rows(void);
+
 /* 1 if psattn_fwd (backward = 0) or psattn_bwd (backward != 0) would run the bf16
  * matrix-core kernels for this meta object, element type, head_dim and scale, 0 if
  * the call would run on the slow generic kernels, negative status for a NULL meta. */

@@ -19,6 +19,7 @@ EXPORTS = [
     "psattn_meta_allowed_pairs", "psattn_fwd", "psattn_bwd", "psattn_bwd_workspace_bytes",
     "psattn_kernel_name", "psattn_strerror", "psattn_profile_enable", "psattn_profile_read",
     "psattn_free_meta_async", "psattn_trim_pool", "psattn_uses_mfma",
+    "psattn_bwd_static", "psattn_bwd_static_max_rows",
 ]
 
 
@@ -58,6 +59,9 @@ def load_library():
     lib.psattn_fwd.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp]
     lib.psattn_bwd.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                C.c_size_t, vp]
+    lib.psattn_bwd_static.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.psattn_bwd_static_max_rows.argtypes = []
+    lib.psattn_bwd_static_max_rows.restype = C.c_size_t
     lib.psattn_bwd_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.psattn_bwd_workspace_bytes.restype = C.c_size_t
     lib.psattn_kernel_name.argtypes = [i32, i32]
@@ -273,6 +277,28 @@ def psattn_bwd(meta: Meta, Q, K, V, O, dO, LSE, scale, dQ=None, dK=None, dV=None
                         dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(), ws_bytes, _stream_ptr(stream))
     _check(st, "psattn_bwd")
     return dQ, dK, dV
+
+
+def psattn_bwd_static(meta: Meta, Q, K, V, O, dO, LSE, scale, dQ, dK, dV, stream=None):
+    """psattn_bwd on the library's static scratch: allocates nothing, so the outputs must be given."""
+    import torch
+    lib = load_library()
+    T, Hq, d = Q.shape
+    Hkv = K.shape[1]
+    _check_tensor(Q, "Q", (meta.total_tokens, Hq, d), None)
+    for t, name, shape in ((K, "K", (T, Hkv, d)), (V, "V", (T, Hkv, d)), (O, "O", Q.shape), (dO, "dO", Q.shape),
+                           (dQ, "dQ", Q.shape), (dK, "dK", K.shape), (dV, "dV", K.shape)):
+        _check_tensor(t, name, shape, Q.dtype)
+    _check_tensor(LSE, "LSE", (Hq, T), torch.float32)
+    st = lib.psattn_bwd_static(meta.handle, _dtype_code(Q), Hq, Hkv, d, float(scale), Q.data_ptr(), K.data_ptr(),
+                               V.data_ptr(), O.data_ptr(), dO.data_ptr(), LSE.data_ptr(), dQ.data_ptr(),
+                               dK.data_ptr(), dV.data_ptr(), _stream_ptr(stream))
+    _check(st, "psattn_bwd_static")
+    return dQ, dK, dV
+
+
+def psattn_bwd_static_max_rows() -> int:
+    return int(load_library().psattn_bwd_static_max_rows())
 
 
 def psattn_trim_pool() -> None:
