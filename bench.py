@@ -229,6 +229,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations and the paired baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--sweep", action="store_true", help="prefix x completion length grid instead of the configurations")
+    ap.add_argument("--dq-atomics-probe", action="store_true",
+                    help="time the fp32 atomic adds a one-pass backward would need for dQ, on every configuration")
     ap.add_argument("--copy-probe", action="store_true",
                     help="run a plain 1 GiB device copy 5 times and exit (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -255,6 +257,32 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4,
                           "launches": 5}))
+        return
+    if args.dq_atomics_probe:
+        # the memory operations a one-pass backward would add for dQ, timed alone (see include/psattn.h)
+        res = {}
+        for name in ("cfg2", "cfg3", "cfg4", "cfg5"):
+            wx = W.make_workload(name)
+            meta = ps.psattn_build_meta(wx.offset, wx.prefix_len, wx.chosen_len, wx.rejected_len, wx.total_tokens)
+            acc = torch.zeros((wx.total_tokens, wx.n_q_heads, 128), dtype=torch.float32, device="cuda")
+            r = {}
+            for mode, label in ((0, "atomic_add_ms"), (1, "plain_store_ms")):
+                ts = []
+                for _ in range(4):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    ps.psattn_probe_dq_atomics(meta, wx.n_q_heads, wx.n_kv_heads, acc, mode)
+                    b.record()
+                    torch.cuda.synchronize()
+                    ts.append(a.elapsed_time(b))
+                r[label] = round(min(ts[1:]), 4)
+            n_visits = int(meta.tiles(ps.GRID_BWD)["n_entries"]) * wx.n_q_heads
+            r["tile_visits"] = n_visits
+            r["payload_GB"] = round(n_visits * 64 * 128 * 4 / 1e9, 3)
+            res[name] = r
+            meta.free()
+            del acc
+        print(json.dumps({"metric": "dQ accumulation traffic of a one-pass backward, alone", "unit": "ms", "configs": res}))
         return
     if args.sweep:
         print(json.dumps({"metric": "attention fwd+bwd ms, prefix-shared vs paired, one sample", "unit": "ms",

@@ -227,6 +227,17 @@ int psattn_uses_mfma(const psattn_meta* meta, int32_t dt, int32_t head_dim, floa
 int psattn_profile_enable(int32_t on);
 int psattn_profile_read(double* sum_ms, int64_t* count);
 
+/*
+ * Measurement aid (no part of the computation): issues the memory operations that a
+ * one-pass backward would add for dQ, and nothing else.  One workgroup per (k-tile,
+ * kv-head) walks the k-major tile list of the default grid and adds (mode 0: fp32 atomic
+ * add, mode 1: plain store) a 64 x 128 fp32 tile into acc [T, n_q_heads, 128] (device)
+ * for every (q-tile, q-head) it visits.  Timing it against the separate dQ pass decides
+ * between the two backward designs.  acc is modified.
+ */
+int psattn_probe_dq_atomics(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads, float* acc,
+                            int32_t mode, void* hip_stream);
+
 /* Name of the kernel that psattn_fwd / psattn_bwd launched most recently in this
  * process for the given pass (0 = forward, 1 = delta, 2 = dQ, 3 = dK/dV), for profilers
  * and benchmarks; before any launch of that pass, the kernel a default-grid call with

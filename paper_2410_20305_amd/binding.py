@@ -19,7 +19,7 @@ EXPORTS = [
     "psattn_meta_allowed_pairs", "psattn_fwd", "psattn_bwd", "psattn_bwd_workspace_bytes",
     "psattn_kernel_name", "psattn_strerror", "psattn_profile_enable", "psattn_profile_read",
     "psattn_free_meta_async", "psattn_trim_pool", "psattn_uses_mfma",
-    "psattn_bwd_static", "psattn_bwd_static_max_rows",
+    "psattn_bwd_static", "psattn_bwd_static_max_rows", "psattn_probe_dq_atomics",
 ]
 
 
@@ -62,6 +62,7 @@ def load_library():
     lib.psattn_bwd_static.argtypes = [vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.psattn_bwd_static_max_rows.argtypes = []
     lib.psattn_bwd_static_max_rows.restype = C.c_size_t
+    lib.psattn_probe_dq_atomics.argtypes = [vp, i32, i32, vp, i32, vp]
     lib.psattn_bwd_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.psattn_bwd_workspace_bytes.restype = C.c_size_t
     lib.psattn_kernel_name.argtypes = [i32, i32]
@@ -299,6 +300,15 @@ def psattn_bwd_static(meta: Meta, Q, K, V, O, dO, LSE, scale, dQ, dK, dV, stream
 
 def psattn_bwd_static_max_rows() -> int:
     return int(load_library().psattn_bwd_static_max_rows())
+
+
+def psattn_probe_dq_atomics(meta: Meta, n_q_heads, n_kv_heads, acc, mode, stream=None) -> None:
+    """Measurement aid: the dQ memory operations of a one-pass backward (see include/psattn.h)."""
+    if tuple(acc.shape) != (meta.total_tokens, n_q_heads, 128) or not acc.is_cuda or not acc.is_contiguous():
+        raise ValueError("acc must be a contiguous float32 device tensor [T, n_q_heads, 128]")
+    st = load_library().psattn_probe_dq_atomics(meta.handle, int(n_q_heads), int(n_kv_heads), acc.data_ptr(),
+                                                int(mode), _stream_ptr(stream))
+    _check(st, "psattn_probe_dq_atomics")
 
 
 def psattn_trim_pool() -> None:

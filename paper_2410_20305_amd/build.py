@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsattn.so")
 SOURCES = ["psattn_meta.cpp", "psattn_api.hip", "psattn_generic.hip", "psattn_mfma_fwd.hip", "psattn_mfma_bwd.hip",
-           "psattn_mfma_dkdv.hip", "psattn_bwd_static.hip"]
+           "psattn_mfma_dkdv.hip", "psattn_bwd_static.hip", "psattn_probe.hip"]
 
 # Packed-fp32 VALU instructions are switched off for all device code (the compiler
 # otherwise forms them from ordinary float arithmetic).
@@ -18,7 +18,9 @@ DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 # The dK/dV kernel manages the accumulation registers a[0:191] itself (see the head of its
 # source file); the compiler must not park spilled values there.
-SOURCE_FLAGS = {"psattn_mfma_dkdv.hip": ["-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"]}
+SOURCE_FLAGS = {"psattn_mfma_dkdv.hip": ["-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"],
+                # the probe measures the hardware fp32 atomic add, not a compare-and-swap loop
+                "psattn_probe.hip": ["-munsafe-fp-atomics"]}
 
 def hipcc() -> str:
     for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):

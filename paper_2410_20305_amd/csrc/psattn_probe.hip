@@ -1,0 +1,54 @@
+// Measurement aid for one design decision: should the backward be ONE k-major pass that
+// also accumulates dQ with fp32 atomic adds, instead of the separate q-major dQ pass?
+// This kernel issues exactly the memory operations such a pass would add, and nothing else:
+// one workgroup per (k-tile, kv-head) walks the k-major tile list of the block mask and,
+// for every (q-tile, q-head) it visits, adds a 64 x 128 fp32 tile into a [T, Hq, 128]
+// accumulator.  Lanes are laid out as the 32x32 MFMA accumulator would hand the values
+// over (wave w owns head dims 32 w .. 32 w + 31, one lane per head dim, 16 query rows per
+// lane and 32-query block), so each wave instruction covers two full 128-byte lines: the
+// most coalesced form this access pattern has.  mode 0: atomic adds; mode 1: plain stores
+// of the same addresses (what a write-partials-then-reduce scheme would cost at least).
+#include <hip/hip_runtime.h>
+
+#include "psattn_internal.h"
+
+namespace psattn {
+namespace {
+
+__global__ __launch_bounds__(256) void psattn_dq_atomics_probe(DeviceMeta meta, int Hq, int Hkv, float* acc, int mode) {
+    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, c32 = l & 31, g = l >> 5;
+    const int G = Hq / Hkv, T = meta.T;
+    const DeviceCsr& csr = meta.bwd;
+    const RowLaunch rl = csr.launch[blockIdx.x / Hkv];
+    const int kvh = blockIdx.x % Hkv;
+    for (int k = rl.count - 1; k >= 0; --k) {  // same walk as the dK/dV kernel: last q-tile first, heads innermost
+        const int q0 = (csr.entry[rl.begin + k] >> 2) * csr.tile_q;
+        for (int hh = 0; hh < G; ++hh) {
+            const int h = kvh * G + hh;
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int q = min(q0 + 32 * b + (i >> 2) * 8 + 4 * g + (i & 3), T - 1);
+                    float* p = acc + (static_cast<size_t>(q) * Hq + h) * 128 + 32 * w + c32;
+                    if (mode == 0) unsafeAtomicAdd(p, 1.0f);
+                    else __builtin_nontemporal_store(1.0f, p);
+                }
+        }
+    }
+}
+
+}  // namespace
+}  // namespace psattn
+
+extern "C" int psattn_probe_dq_atomics(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads, float* acc,
+                                       int32_t mode, void* hip_stream) {
+    if (!meta || !acc || n_q_heads <= 0 || n_kv_heads <= 0 || n_q_heads % n_kv_heads != 0) return PSATTN_EINVAL;
+    if (!meta->on_device) return PSATTN_ENODEVICE;
+    if (meta->bwd.tile_q != psattn::kBwdTileQ || meta->bwd.tile_k != psattn::kBwdTileK) return PSATTN_EUNSUPPORTED;
+    const unsigned grid = static_cast<unsigned>(meta->dev.bwd.n_rows) * n_kv_heads;
+    if (grid == 0) return PSATTN_OK;
+    psattn::psattn_dq_atomics_probe<<<grid, 256, 0, static_cast<hipStream_t>(hip_stream)>>>(meta->dev, n_q_heads, n_kv_heads,
+                                                                                           acc, mode);
+    return hipGetLastError() == hipSuccess ? PSATTN_OK : PSATTN_EHIP;
+}
