@@ -15,7 +15,9 @@ What it follows:
   * ordinary softmax attention on the allowed pairs (Section 3.1 states that
     nothing else changes), with the textbook explicit backward;
   * the per-mini-batch block mask of Section 3.1 (blocks with no allowed pair are
-    skipped), as a brute-force classification over the dense boolean mask.
+    skipped), as a brute-force classification over the dense boolean mask;
+  * First-Fit-Decreasing packing of whole samples into fixed-length rows
+    (Section 4.3.2), as the textbook loop.
 
 Readings where the paper is silent (all restated where they are used):
   - start indices are row-absolute positions (they are compared with q and kv);
@@ -34,7 +36,9 @@ closed-form pair counts and the paper's two ideal-speedup footnotes, pure-Python
 brute force, torch fp64 scaled_dot_product_attention (+autograd), finite
 differences, the no-contamination invariant against plain causal attention on
 [prompt|chosen] and [prompt|rejected], packing independence, response swap
-symmetry, GQA expansion.  No function here is unpinned.
+symmetry, GQA expansion; for the packer a hand-worked example, the first-fit
+property checked by replay, and the 11/9 OPT + 6/9 bound against a brute-force
+optimum.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -357,3 +361,35 @@ def forward_rows(Q, K, V, scale, I_chosen, I_rejected, D, h, rows):
         O[n] = o[0]
         LSE[n] = lse[0]
     return O, LSE
+
+
+# --------------------------------------------------------------------------
+# packing (Section 4.3.2: First-Fit-Decreasing sampler; the unit is a whole
+# sample, Section 3.2)
+# --------------------------------------------------------------------------
+def ffd_pack(lengths, row_len, max_rows=0):
+    """First-Fit-Decreasing, written out: take the units from the longest to the
+    shortest (equal lengths in their original order); put each into the first row,
+    in order of opening, that still has room, directly behind what the row already
+    holds; open a new row when none has room (with max_rows > 0: leave the unit out
+    when that many rows are open).  Returns (offset [n] with -1 for units left out,
+    n_rows): offset = row * row_len + position in the row."""
+    n = len(lengths)
+    by_len = sorted(range(n), key=lambda i: -int(lengths[i]))   # Python's sort is stable
+    fill = []                                                   # tokens used per open row
+    offset = [-1] * n
+    for i in by_len:
+        need = int(lengths[i])
+        if need <= 0 or need > row_len:
+            raise ValueError("unit %d does not fit a row" % i)
+        placed = False
+        for r in range(len(fill)):
+            if fill[r] + need <= row_len:
+                offset[i] = r * row_len + fill[r]
+                fill[r] += need
+                placed = True
+                break
+        if not placed and (max_rows == 0 or len(fill) < max_rows):
+            offset[i] = len(fill) * row_len
+            fill.append(need)
+    return np.asarray(offset, dtype=np.int32), len(fill)
