@@ -158,6 +158,32 @@ int psattn_meta_copy_key_desc(const psattn_meta* meta, int32_t* key_hi);
 int psattn_meta_allowed_pairs(const psattn_meta* meta, int64_t* n_allowed);
 
 /*
+ * First-Fit-Decreasing packing of samples into rows of row_len tokens (Section 4.3.2: an
+ * FFD-based sampler packs each mini-batch; the packing length is batch size x maximum
+ * sequence length and batches are padded to it).  The packing unit is a whole sample
+ * (prompt + chosen + rejected): units are taken in order of decreasing length, equal
+ * lengths in their original order, and each goes to the lowest-numbered row that still
+ * has room, at the first free position of that row; a new row is opened only when no
+ * open row has room.  Host only, integer only, O(n log n).
+ *
+ *   max_rows = 0: as many rows as needed.  max_rows > 0: at most that many rows (the
+ *       fixed packing length of a mini-batch); a unit that fits nowhere gets offset -1.
+ *   offset [n_samples] (host, out): flat start token of every sample, row * row_len +
+ *       position in the row, in the caller's sample order; -1 = left out.
+ *   order  [n_samples] (host, out): sample indices sorted by offset (left-out samples last).
+ *       psattn_build_meta wants its sample table sorted by offset: pass offset[order[k]],
+ *       prefix_len[order[k]], ... for the k placed samples, and total_tokens = *n_rows * row_len.
+ *   n_rows, padding_tokens (host, out, may be NULL): rows opened; row capacity not covered
+ *       by a placed sample.
+ * Errors: PSATTN_EINVAL (null array, negative length, empty sample, row_len <= 0),
+ * PSATTN_ERANGE (a sample longer than a row), PSATTN_EUNSUPPORTED (flat offsets would
+ * not fit int32).
+ */
+int psattn_pack_ffd(int32_t n_samples, const int32_t* prefix_len, const int32_t* chosen_len,
+                    const int32_t* rejected_len, int32_t row_len, int32_t max_rows,
+                    int32_t* offset, int32_t* order, int32_t* n_rows, int64_t* padding_tokens);
+
+/*
  * Forward: O = softmax(scale * Q K^T restricted to allowed pairs) V and
  * LSE[h, q] = log sum_kv exp(scale * Q_q . K_kv) (natural log).  SKIPPED tiles are
  * never computed (Section 3.1).  dt selects the element type of Q, K, V, O

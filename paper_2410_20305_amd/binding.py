@@ -20,6 +20,7 @@ EXPORTS = [
     "psattn_kernel_name", "psattn_strerror", "psattn_profile_enable", "psattn_profile_read",
     "psattn_free_meta_async", "psattn_trim_pool", "psattn_uses_mfma",
     "psattn_bwd_static", "psattn_bwd_static_max_rows", "psattn_probe_dq_atomics",
+    "psattn_pack_ffd",
 ]
 
 
@@ -63,6 +64,7 @@ def load_library():
     lib.psattn_bwd_static_max_rows.argtypes = []
     lib.psattn_bwd_static_max_rows.restype = C.c_size_t
     lib.psattn_probe_dq_atomics.argtypes = [vp, i32, i32, vp, i32, vp]
+    lib.psattn_pack_ffd.argtypes = [i32, vp, vp, vp, i32, i32, vp, vp, pi32, C.POINTER(i64)]
     lib.psattn_bwd_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.psattn_bwd_workspace_bytes.restype = C.c_size_t
     lib.psattn_kernel_name.argtypes = [i32, i32]
@@ -201,6 +203,23 @@ def psattn_build_meta(offset, prefix_len, chosen_len, rejected_len, total_tokens
                                    _stream_ptr(stream), C.byref(h))
         _check(st, "psattn_build_meta")
     return Meta(h, total_tokens, not host_only)
+
+
+def psattn_pack_ffd(prefix_len, chosen_len, rejected_len, row_len, max_rows=0):
+    """First-Fit-Decreasing packing.  Returns dict(offset [n] (-1 = left out), order [n], n_rows,
+    padding_tokens)."""
+    lib = load_library()
+    p, c, r = _i32(prefix_len), _i32(chosen_len), _i32(rejected_len)
+    n = p.shape[0]
+    if not (c.shape[0] == r.shape[0] == n):
+        raise ValueError("sample arrays differ in length")
+    offset = np.zeros(max(1, n), dtype=np.int32)
+    order = np.zeros(max(1, n), dtype=np.int32)
+    n_rows, pad = C.c_int32(), C.c_int64()
+    st = lib.psattn_pack_ffd(n, p.ctypes.data, c.ctypes.data, r.ctypes.data, int(row_len), int(max_rows),
+                             offset.ctypes.data, order.ctypes.data, C.byref(n_rows), C.byref(pad))
+    _check(st, "psattn_pack_ffd")
+    return dict(offset=offset[:n], order=order[:n], n_rows=n_rows.value, padding_tokens=pad.value)
 
 
 def _dtype_code(t):
