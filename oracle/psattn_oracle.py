@@ -136,6 +136,75 @@ def response_id_mask(q, kv, R):
     return same_unit & (kv <= q)
 
 
+# ---- any number of responses per prompt
+# Section 2.2 notes the kinship of the prefix-sharing mask with tree-structured attention
+# masks: the prompt is the trunk, every response a branch.  A token reads the not-later
+# tokens of its own sample that lie on its path to the root: the prompt, and its own
+# branch.  With two branches this is exactly the mask above.
+def branch_arrays(offset, prefix_len, resp_ptr, resp_len, total_tokens):
+    """Per-token sample id D (-1 = padding) and branch id B (0 = prompt, j = j-th response,
+    counted from 1) for samples [prompt | response 1 | ... | response k]; the responses of
+    sample i are resp_len[resp_ptr[i] : resp_ptr[i + 1]]."""
+    T = int(total_tokens)
+    D = np.full(T, PAD_DOC, dtype=np.int64)
+    B = np.zeros(T, dtype=np.int64)
+    for i in range(len(offset)):
+        t = int(offset[i])
+        lens = [int(prefix_len[i])] + [int(x) for x in resp_len[int(resp_ptr[i]):int(resp_ptr[i + 1])]]
+        if t < 0 or min(lens) < 0 or t + sum(lens) > T:
+            raise ValueError("sample %d out of range" % i)
+        if np.any(D[t:t + sum(lens)] != PAD_DOC):
+            raise ValueError("sample %d overlaps another" % i)
+        for j, n in enumerate(lens):
+            D[t:t + n] = i
+            B[t:t + n] = j
+            t += n
+    return D, B
+
+
+def branch_mask(q, kv, D, B):
+    """allowed(q, kv) for samples with any number of responses."""
+    q, kv = np.asarray(q), np.asarray(kv)
+    same_sample = (D[q] == D[kv]) & (D[q] != PAD_DOC)
+    on_path = (B[kv] == 0) | (B[kv] == B[q])
+    return same_sample & (kv <= q) & on_path
+
+
+def dense_branch_mask(D, B, q_lo=0, q_hi=None, k_lo=0, k_hi=None):
+    T = D.shape[0]
+    q_hi = T if q_hi is None else q_hi
+    k_hi = T if k_hi is None else k_hi
+    q = np.arange(q_lo, q_hi, dtype=np.int64)[:, None]
+    kv = np.arange(k_lo, k_hi, dtype=np.int64)[None, :]
+    return branch_mask(q, kv, D, B)
+
+
+def branch_token_descriptors(D, B):
+    """Per-token (s, hole_lo, hole_hi) as int32 [T, 3] for any number of responses: s = first
+    token of the sample; the keys in [s, q] that a token of response j >= 2 must not read are
+    the earlier responses, one contiguous range [first token behind the prompt, first token
+    of response j); (0, 0) for everything else; s = INT32_MAX for padding."""
+    T = D.shape[0]
+    desc = np.zeros((T, 3), dtype=np.int32)
+    first_of_sample, first_of_branch = {}, {}
+    for t in range(T):                      # first positions, in one sweep
+        if D[t] != PAD_DOC:
+            first_of_sample.setdefault(int(D[t]), t)
+            first_of_branch.setdefault((int(D[t]), int(B[t])), t)
+    for t in range(T):
+        d, b = int(D[t]), int(B[t])
+        if d == PAD_DOC:
+            desc[t, 0] = PAD_START
+            continue
+        desc[t, 0] = first_of_sample[d]
+        if b >= 2:
+            # first token behind the prompt (if every earlier response is empty that is the
+            # token's own response, and the range is empty)
+            desc[t, 1] = min(first_of_branch[(d, j)] for j in range(1, b + 1) if (d, j) in first_of_branch)
+            desc[t, 2] = first_of_branch[(d, b)]
+    return desc
+
+
 def dense_mask(I_chosen, I_rejected, D, q_lo=0, q_hi=None, k_lo=0, k_hi=None):
     """Boolean matrix allowed[q - q_lo, kv - k_lo] of Algorithm 3."""
     T = D.shape[0]
@@ -160,8 +229,10 @@ def count_allowed(I_chosen, I_rejected, D, stripe=256):
 # block mask (Section 3.1: computed once per mini-batch, blocks with no allowed
 # pair are skipped)
 # --------------------------------------------------------------------------
-def classify_tiles(I_chosen, I_rejected, D, tile_q, tile_k):
+def classify_tiles(I_chosen, I_rejected, D, tile_q, tile_k, mask=None):
     """Brute-force class of every (q-tile, k-tile) of the global grid.
+    `mask(q_lo, q_hi, k_lo, k_hi)`, if given, replaces the two-response dense mask
+    (see dense_branch_mask for samples with any number of responses).
 
     Tile t covers tokens [t*tile, min((t+1)*tile, T)).  SKIPPED: no allowed
     pair.  FULL: the unclipped tile_q x tile_k rectangle lies inside the buffer
@@ -176,7 +247,7 @@ def classify_tiles(I_chosen, I_rejected, D, tile_q, tile_k):
         q_lo, q_hi = tq * tile_q, min(T, (tq + 1) * tile_q)
         # keys beyond the last query of the stripe fail the causal clause
         k_end = q_hi
-        stripe = dense_mask(I_chosen, I_rejected, D, q_lo, q_hi, 0, k_end)
+        stripe = mask(q_lo, q_hi, 0, k_end) if mask else dense_mask(I_chosen, I_rejected, D, q_lo, q_hi, 0, k_end)
         for tk in range((k_end + tile_k - 1) // tile_k):
             k_lo, k_hi = tk * tile_k, min(T, (tk + 1) * tile_k)
             blk = stripe[:, k_lo:min(k_hi, k_end)]
@@ -289,7 +360,7 @@ def _blocks(D, samples):
     return out
 
 
-def forward(Q, K, V, scale, I_chosen, I_rejected, D, heads=None, samples=None, flat=False):
+def forward(Q, K, V, scale, I_chosen, I_rejected, D, heads=None, samples=None, flat=False, mask=None):
     """Forward over the flat buffer.
 
     Q [T, Hq, d], K, V [T, Hkv, d] (any float dtype; used as float64).
@@ -297,7 +368,8 @@ def forward(Q, K, V, scale, I_chosen, I_rejected, D, heads=None, samples=None, f
     `heads` / `samples` restrict the work, everything not requested) hold
     O = 0 and LSE = -inf.  flat=True evaluates the whole T x T mask at once
     instead of one dense block per document (tiny inputs only); the document
-    clause makes both forms identical.
+    clause makes both forms identical.  `mask(q_lo, q_hi, k_lo, k_hi)`, if given,
+    replaces the two-response dense mask (I_chosen, I_rejected are then unused).
     """
     T, Hq, d = Q.shape
     Hkv = K.shape[1]
@@ -308,7 +380,7 @@ def forward(Q, K, V, scale, I_chosen, I_rejected, D, heads=None, samples=None, f
     for h in (range(Hq) if heads is None else heads):
         g = h // G
         for lo, hi in ranges:
-            allowed = dense_mask(I_chosen, I_rejected, D, lo, hi, lo, hi)
+            allowed = mask(lo, hi, lo, hi) if mask else dense_mask(I_chosen, I_rejected, D, lo, hi, lo, hi)
             o, lse, _ = forward_block(_as64(Q[lo:hi, h]), _as64(K[lo:hi, g]), _as64(V[lo:hi, g]),
                                       allowed, scale)
             O[lo:hi, h] = o
@@ -316,7 +388,7 @@ def forward(Q, K, V, scale, I_chosen, I_rejected, D, heads=None, samples=None, f
     return O, LSE
 
 
-def backward(Q, K, V, dO, scale, I_chosen, I_rejected, D, heads=None, samples=None, flat=False):
+def backward(Q, K, V, dO, scale, I_chosen, I_rejected, D, heads=None, samples=None, flat=False, mask=None):
     """Backward over the flat buffer from the oracle's own O and LSE.
 
     Returns dict with dQ [T, Hq, d], dK, dV [T, Hkv, d], O, LSE [Hq, T],
@@ -333,7 +405,7 @@ def backward(Q, K, V, dO, scale, I_chosen, I_rejected, D, heads=None, samples=No
     for h in (range(Hq) if heads is None else heads):
         g = h // G
         for lo, hi in ranges:
-            allowed = dense_mask(I_chosen, I_rejected, D, lo, hi, lo, hi)
+            allowed = mask(lo, hi, lo, hi) if mask else dense_mask(I_chosen, I_rejected, D, lo, hi, lo, hi)
             dq, dk, dv, o, lse, delta = backward_block(
                 _as64(Q[lo:hi, h]), _as64(K[lo:hi, g]), _as64(V[lo:hi, g]), _as64(dO[lo:hi, h]),
                 allowed, scale)
