@@ -353,6 +353,41 @@ def main():
                 del rx
             torch.cuda.empty_cache()
         out["all_configs"] = extras
+        # First-Fit-Decreasing packing of the same samples (Section 4.3.2) against the in-order greedy rule
+        ffd = {}
+        for name in ("cfg4", "cfg5"):
+            wx = W.make_workload(name)
+            t0 = time.perf_counter()
+            pk = ps.psattn_pack_ffd(wx.prefix_len, wx.chosen_len, wx.rejected_len, wx.row_len)
+            pack_ms = (time.perf_counter() - t0) * 1e3
+            wf = W.with_layout(wx, pk["offset"], pk["order"], pk["n_rows"] * wx.row_len, name=name + "-ffd")
+            rf = Runner(wf, None, seed=wx.seed)
+            ms_f, pp_f, pst_f = rf.timed(max(5, min(args.steps, 20)), 3)
+            ffd[name] = dict(rows_greedy=wx.total_tokens // wx.row_len, rows_ffd=pk["n_rows"],
+                             padding_fraction_greedy=round(1 - wx.unique_tokens / wx.total_tokens, 4),
+                             padding_fraction_ffd=round(pk["padding_tokens"] / max(1, pk["n_rows"] * wx.row_len), 4),
+                             pack_ms=round(pack_ms, 4), ms_per_step_ffd=round(ms_f, 4),
+                             ms_per_step_greedy=extras[name]["ms_per_step"],
+                             pct_mfma_peak_ffd=round(100 * rf.flops / (ms_f * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2))
+            # a larger pool drawn from the same length distribution (host only): rows needed by either rule
+            cfg = W.CONFIGS[name]
+            rng = np.random.default_rng(cfg["seed"] + 77)
+            n_pool = 512
+            P, Cc, R = (rng.integers(cfg[k][0], cfg[k][1], size=n_pool, endpoint=True).astype(np.int32) for k in "pcr")
+            lens = P.astype(np.int64) + Cc + R
+            rows_g, fill = 1, 0
+            for L in lens:                     # in-order greedy: close the row when the next sample does not fit
+                if fill + L > wx.row_len:
+                    rows_g, fill = rows_g + 1, 0
+                fill += int(L)
+            pkp = ps.psattn_pack_ffd(P, Cc, R, wx.row_len)
+            ffd[name]["pool_%d_samples" % n_pool] = dict(
+                rows_greedy=rows_g, rows_ffd=pkp["n_rows"],
+                padding_fraction_greedy=round(1 - int(lens.sum()) / (rows_g * wx.row_len), 4),
+                padding_fraction_ffd=round(1 - int(lens.sum()) / (pkp["n_rows"] * wx.row_len), 4))
+            del rf
+            torch.cuda.empty_cache()
+        out["ffd_packing"] = ffd
         out["paper_context"] = "paper reports 1.1-1.5x (1.3-1.6x packed) end-to-end training speedup on 8xH100"
 
     if not args.no_cpu:

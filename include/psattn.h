@@ -124,6 +124,29 @@ int psattn_build_meta_host(int32_t n_samples, const int32_t* offset, const int32
                            int32_t total_tokens, int32_t tile_q, int32_t tile_k,
                            int32_t bwd_tile_q, int32_t bwd_tile_k, psattn_meta** out);
 
+/*
+ * The same block mask for samples with any number of responses per prompt,
+ * [prompt | response 1 | ... | response k]: every response attends to the prompt and
+ * to itself, never to another response (Section 2.2 relates the prefix-sharing mask to
+ * tree-structured attention masks: the prompt is the trunk, the responses are
+ * branches).  k = 2 is the paper's [prompt | chosen | rejected]; k = 1 and k = 0 are
+ * plain causal documents.  The responses of sample i have lengths
+ * resp_len[resp_ptr[i] .. resp_ptr[i + 1]) (host arrays, resp_ptr[0] = 0, CSR style).
+ * Per-token descriptors: tokens of response j >= 2 get (hole_lo, hole_hi) = (first token
+ * behind the prompt, first token of response j), everything else (0, 0).  Everything
+ * else (grids, errors, upload, ownership) is as for psattn_build_meta, and the object is
+ * used with the same psattn_fwd / psattn_bwd.
+ */
+int psattn_build_meta_multi(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                            const int32_t* resp_ptr, /* host [n_samples + 1] */
+                            const int32_t* resp_len, /* host [resp_ptr[n_samples]] */
+                            int32_t total_tokens, int32_t tile_q, int32_t tile_k,
+                            int32_t bwd_tile_q, int32_t bwd_tile_k, void* hip_stream, psattn_meta** out);
+int psattn_build_meta_multi_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                                 const int32_t* resp_ptr, const int32_t* resp_len, int32_t total_tokens,
+                                 int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
+                                 psattn_meta** out);
+
 /* Releases the object; its buffers return to the library's pool.  The caller must
  * make sure no kernel that uses it is still running.  NULL is accepted. */
 int psattn_free_meta(psattn_meta* meta);
@@ -154,7 +177,8 @@ int psattn_meta_copy_tok_desc(const psattn_meta* meta, int32_t* tok_desc);
  * 0 for padding).  This is the mask seen from the key side, used by the dK/dV pass. */
 int psattn_meta_copy_key_desc(const psattn_meta* meta, int32_t* key_hi);
 /* Exact number of allowed (q, kv) pairs, from the closed form
- * sum_i tri(p) + c*p + tri(c) + r*p + tri(r), tri(n) = n(n+1)/2. */
+ * sum_i tri(p) + sum_responses (len * p + tri(len)), tri(n) = n(n+1)/2
+ * (two responses: tri(p) + c*p + tri(c) + r*p + tri(r)). */
 int psattn_meta_allowed_pairs(const psattn_meta* meta, int64_t* n_allowed);
 
 /*

@@ -20,7 +20,7 @@ EXPORTS = [
     "psattn_kernel_name", "psattn_strerror", "psattn_profile_enable", "psattn_profile_read",
     "psattn_free_meta_async", "psattn_trim_pool", "psattn_uses_mfma",
     "psattn_bwd_static", "psattn_bwd_static_max_rows", "psattn_probe_dq_atomics",
-    "psattn_pack_ffd",
+    "psattn_pack_ffd", "psattn_build_meta_multi", "psattn_build_meta_multi_host",
 ]
 
 
@@ -48,6 +48,8 @@ def load_library():
     pi32 = C.POINTER(C.c_int32)
     lib.psattn_build_meta.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
     lib.psattn_build_meta_host.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp)]
+    lib.psattn_build_meta_multi.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
+    lib.psattn_build_meta_multi_host.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp)]
     lib.psattn_free_meta.argtypes = [vp]
     lib.psattn_free_meta_async.argtypes = [vp, vp]
     lib.psattn_trim_pool.argtypes = []
@@ -202,6 +204,28 @@ def psattn_build_meta(offset, prefix_len, chosen_len, rejected_len, total_tokens
                                    int(total_tokens), tile_q, tile_k, bwd_tile_q, bwd_tile_k,
                                    _stream_ptr(stream), C.byref(h))
         _check(st, "psattn_build_meta")
+    return Meta(h, total_tokens, not host_only)
+
+
+def psattn_build_meta_multi(offset, prefix_len, resp_ptr, resp_len, total_tokens, tile_q=0, tile_k=0,
+                            bwd_tile_q=0, bwd_tile_k=0, stream=None, host_only=False) -> Meta:
+    """Block mask for samples with any number of responses per prompt (CSR-style resp_ptr / resp_len)."""
+    lib = load_library()
+    off, p, ptr, rl = _i32(offset), _i32(prefix_len), _i32(resp_ptr), _i32(resp_len)
+    n = off.shape[0]
+    if p.shape[0] != n or ptr.shape[0] != n + 1 or (n and rl.shape[0] != int(ptr[-1])):
+        raise ValueError("sample arrays differ in length")
+    rl_ptr = rl.ctypes.data if rl.shape[0] else None
+    h = C.c_void_p()
+    if host_only:
+        st = lib.psattn_build_meta_multi_host(n, off.ctypes.data, p.ctypes.data, ptr.ctypes.data, rl_ptr,
+                                              int(total_tokens), tile_q, tile_k, bwd_tile_q, bwd_tile_k, C.byref(h))
+        _check(st, "psattn_build_meta_multi_host")
+    else:
+        st = lib.psattn_build_meta_multi(n, off.ctypes.data, p.ctypes.data, ptr.ctypes.data, rl_ptr,
+                                         int(total_tokens), tile_q, tile_k, bwd_tile_q, bwd_tile_k,
+                                         _stream_ptr(stream), C.byref(h))
+        _check(st, "psattn_build_meta_multi")
     return Meta(h, total_tokens, not host_only)
 
 

@@ -329,6 +329,24 @@ int psattn_build_meta(int32_t n_samples, const int32_t* offset, const int32_t* p
     return PSATTN_OK;
 }
 
+int psattn_build_meta_multi(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                            const int32_t* resp_ptr, const int32_t* resp_len, int32_t total_tokens,
+                            int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
+                            void* hip_stream, psattn_meta** out) {
+    psattn_meta* m = nullptr;
+    int rc = build_host_multi(n_samples, offset, prefix_len, resp_ptr, resp_len, total_tokens, tile_q, tile_k,
+                              bwd_tile_q, bwd_tile_k, &m);
+    if (rc != PSATTN_OK) return rc;
+    rc = upload(m, static_cast<hipStream_t>(hip_stream));
+    if (rc != PSATTN_OK) {
+        release_meta(m, static_cast<hipStream_t>(hip_stream));
+        *out = nullptr;
+        return rc;
+    }
+    *out = m;
+    return PSATTN_OK;
+}
+
 int psattn_free_meta(psattn_meta* meta) { return release_meta(meta, nullptr); }
 
 int psattn_free_meta_async(psattn_meta* meta, void* hip_stream) {

@@ -87,6 +87,11 @@ int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_l
                int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
                psattn_meta** out);
 
+int build_host_multi(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                     const int32_t* resp_ptr, const int32_t* resp_len, int32_t total_tokens,
+                     int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
+                     psattn_meta** out);
+
 struct AttnArgs {
     DeviceMeta meta;
     int32_t Hq, Hkv, d;

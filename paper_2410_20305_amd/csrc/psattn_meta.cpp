@@ -31,25 +31,34 @@ int64_t causal_pairs(int64_t qa, int64_t qb, int64_t ka, int64_t kb) {
     return n;
 }
 
+// A sample is [prompt | response 1 | ... | response k]; resp[j] is the first token of
+// response j + 1, resp[k] == e.  The paper's case is k = 2 (chosen, rejected).
 struct Sample {
-    int64_t o, C, R, e;  // start, chosen start, rejected start, end
+    int64_t o, C, e;          // start, first token behind the prompt, end
+    const int64_t* resp;      // k + 1 ascending positions, resp[0] == C
+    int32_t k;
 };
 
-// Allowed pairs of one sample inside the rectangle [qa, qb) x [ka, kb)
-// (Algorithm 1: prompt and chosen queries are plain causal; rejected queries see
-// the prompt and the rejected tokens before them).
+inline int64_t overlap(int64_t a0, int64_t a1, int64_t b0, int64_t b1) {
+    return std::max<int64_t>(0, std::min(a1, b1) - std::max(a0, b0));
+}
+
+// Allowed pairs of one sample inside the rectangle [qa, qb) x [ka, kb).  Everything not
+// later than the query is allowed (Algorithm 1's causal clause) except, for a query in
+// response j, the keys of the responses before it: they form one range [C, start of
+// response j) and all lie before the query, so each removes one causal pair.
 int64_t sample_pairs(const Sample& s, int64_t qa, int64_t qb, int64_t ka, int64_t kb) {
     qa = std::max(qa, s.o);
     qb = std::min(qb, s.e);
     ka = std::max(ka, s.o);
     kb = std::min(kb, s.e);
     if (qa >= qb || ka >= kb) return 0;
-    int64_t n = causal_pairs(qa, std::min(qb, s.R), ka, kb);
-    int64_t ra = std::max(qa, s.R);
-    if (ra < qb) {
-        int64_t pk = std::min(kb, s.C) - ka;  // prompt keys, all before any rejected query
-        if (pk > 0) n += (qb - ra) * pk;
-        n += causal_pairs(ra, qb, std::max(ka, s.R), kb);
+    int64_t n = causal_pairs(qa, qb, ka, kb);
+    if (s.k >= 2 && qb > s.resp[1] && kb > s.C) {
+        // responses that hold a query of the range, from the second response on
+        int32_t j = static_cast<int32_t>(std::upper_bound(s.resp, s.resp + s.k + 1, qa) - s.resp) - 1;
+        for (j = std::max(j, 1); j < s.k && s.resp[j] < qb; ++j)
+            n -= overlap(qa, qb, s.resp[j], s.resp[j + 1]) * overlap(ka, kb, s.C, s.resp[j]);
     }
     return n;
 }
@@ -139,14 +148,14 @@ void order_rows(TileCsr& g, bool descending) {
 
 }  // namespace
 
-int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
-               const int32_t* chosen_len, const int32_t* rejected_len, int32_t total_tokens,
-               int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
-               psattn_meta** out) {
+int build_host_multi(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                     const int32_t* resp_ptr, const int32_t* resp_len, int32_t total_tokens,
+                     int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
+                     psattn_meta** out) {
     if (!out) return PSATTN_EINVAL;
     *out = nullptr;
     if (n_samples < 0 || total_tokens < 0) return PSATTN_EINVAL;
-    if (n_samples > 0 && (!offset || !prefix_len || !chosen_len || !rejected_len)) return PSATTN_EINVAL;
+    if (n_samples > 0 && (!offset || !prefix_len || !resp_ptr)) return PSATTN_EINVAL;
     if (tile_q < 0 || tile_k < 0 || bwd_tile_q < 0 || bwd_tile_k < 0) return PSATTN_EINVAL;
     if (tile_q == 0) tile_q = kFwdTileQ;
     if (tile_k == 0) tile_k = kFwdTileK;
@@ -158,18 +167,40 @@ int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_l
     for (int32_t t : {tile_q, tile_k, bwd_tile_q, bwd_tile_k})
         if ((T + t - 1) / t >= kMaxTiles) return PSATTN_EUNSUPPORTED;
     std::vector<Sample> samples;
+    std::vector<int64_t> starts;  // response boundaries of all samples, k + 1 per sample
     int64_t prev_end = 0, n_allowed = 0;
     try {
         samples.reserve(n_samples);
-        for (int32_t i = 0; i < n_samples; ++i) {
-            const int64_t o = offset[i], p = prefix_len[i], c = chosen_len[i], r = rejected_len[i];
-            if (o < 0 || p < 0 || c < 0 || r < 0 || p + c + r == 0) return PSATTN_EINVAL;
-            if (o < prev_end) return PSATTN_EOVERLAP;
-            if (o + p + c + r > T) return PSATTN_ERANGE;
-            samples.push_back({o, o + p, o + p + c, o + p + c + r});
-            prev_end = o + p + c + r;
-            n_allowed += tri(p) + c * p + tri(c) + r * p + tri(r);
+        if (n_samples > 0) {
+            if (resp_ptr[0] != 0) return PSATTN_EINVAL;
+            for (int32_t i = 0; i < n_samples; ++i)
+                if (resp_ptr[i + 1] < resp_ptr[i]) return PSATTN_EINVAL;
+            if (resp_ptr[n_samples] > 0 && !resp_len) return PSATTN_EINVAL;
+            starts.reserve(static_cast<size_t>(resp_ptr[n_samples]) + n_samples);
         }
+        std::vector<size_t> first(n_samples);
+        for (int32_t i = 0; i < n_samples; ++i) {
+            const int64_t o = offset[i], p = prefix_len[i];
+            if (o < 0 || p < 0) return PSATTN_EINVAL;
+            if (o < prev_end) return PSATTN_EOVERLAP;
+            first[i] = starts.size();
+            int64_t t = o + p;
+            n_allowed += tri(p);
+            starts.push_back(t);
+            for (int32_t j = resp_ptr[i]; j < resp_ptr[i + 1]; ++j) {
+                const int64_t r = resp_len[j];
+                if (r < 0) return PSATTN_EINVAL;
+                t += r;
+                if (t > T) return PSATTN_ERANGE;
+                n_allowed += r * p + tri(r);
+                starts.push_back(t);
+            }
+            if (t == o) return PSATTN_EINVAL;  // empty sample
+            if (t > T) return PSATTN_ERANGE;
+            samples.push_back({o, o + p, t, nullptr, resp_ptr[i + 1] - resp_ptr[i]});
+            prev_end = t;
+        }
+        for (int32_t i = 0; i < n_samples; ++i) samples[i].resp = starts.data() + first[i];
         std::unique_ptr<psattn_meta> m(new psattn_meta());
         m->T = total_tokens;
         m->n_samples = n_samples;
@@ -178,15 +209,20 @@ int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_l
         m->key_hi.assign(T, 0);
         for (int64_t t = 0; t < T; ++t) m->tok_desc[3 * t] = kPadStart;
         for (const Sample& s : samples) {
-            for (int64_t t = s.o; t < s.e; ++t) {
+            for (int64_t t = s.o; t < s.C; ++t) {
                 m->tok_desc[3 * t] = static_cast<int32_t>(s.o);
-                if (t >= s.R) {  // rejected query: must not see the chosen keys [C, R)
-                    m->tok_desc[3 * t + 1] = static_cast<int32_t>(s.C);
-                    m->tok_desc[3 * t + 2] = static_cast<int32_t>(s.R);
-                }
-                // a chosen key is visible up to the end of the chosen response only
-                m->key_hi[t] = static_cast<int32_t>((t >= s.C && t < s.R) ? s.R : s.e);
+                m->key_hi[t] = static_cast<int32_t>(s.e);  // a prompt key is visible to the whole sample
             }
+            for (int32_t j = 0; j < s.k; ++j)
+                for (int64_t t = s.resp[j]; t < s.resp[j + 1]; ++t) {
+                    m->tok_desc[3 * t] = static_cast<int32_t>(s.o);
+                    if (j >= 1) {  // must not see the responses before its own: keys [C, start of response j)
+                        m->tok_desc[3 * t + 1] = static_cast<int32_t>(s.C);
+                        m->tok_desc[3 * t + 2] = static_cast<int32_t>(s.resp[j]);
+                    }
+                    // a response key is visible up to the end of its own response only
+                    m->key_hi[t] = static_cast<int32_t>(s.resp[j + 1]);
+                }
         }
         if (!classify(samples, T, tile_q, tile_k, m->fwd)) return PSATTN_EUNSUPPORTED;
         order_rows(m->fwd, true);
@@ -201,6 +237,30 @@ int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_l
     return PSATTN_OK;
 }
 
+// The paper's format: two responses per prompt, chosen then rejected.
+int build_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+               const int32_t* chosen_len, const int32_t* rejected_len, int32_t total_tokens,
+               int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
+               psattn_meta** out) {
+    if (!out) return PSATTN_EINVAL;
+    *out = nullptr;
+    if (n_samples < 0) return PSATTN_EINVAL;
+    if (n_samples > 0 && (!chosen_len || !rejected_len)) return PSATTN_EINVAL;
+    try {
+        std::vector<int32_t> ptr(static_cast<size_t>(n_samples) + 1), len(static_cast<size_t>(n_samples) * 2);
+        for (int32_t i = 0; i < n_samples; ++i) {
+            ptr[i] = 2 * i;
+            len[2 * i] = chosen_len[i];
+            len[2 * i + 1] = rejected_len[i];
+        }
+        ptr[n_samples] = 2 * n_samples;
+        return build_host_multi(n_samples, offset, prefix_len, ptr.data(), len.data(), total_tokens, tile_q, tile_k,
+                                bwd_tile_q, bwd_tile_k, out);
+    } catch (const std::bad_alloc&) {
+        return PSATTN_ENOMEM;
+    }
+}
+
 }  // namespace psattn
 
 extern "C" {
@@ -211,6 +271,14 @@ int psattn_build_meta_host(int32_t n_samples, const int32_t* offset, const int32
                            int32_t bwd_tile_q, int32_t bwd_tile_k, psattn_meta** out) {
     return psattn::build_host(n_samples, offset, prefix_len, chosen_len, rejected_len, total_tokens,
                               tile_q, tile_k, bwd_tile_q, bwd_tile_k, out);
+}
+
+int psattn_build_meta_multi_host(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                                 const int32_t* resp_ptr, const int32_t* resp_len, int32_t total_tokens,
+                                 int32_t tile_q, int32_t tile_k, int32_t bwd_tile_q, int32_t bwd_tile_k,
+                                 psattn_meta** out) {
+    return psattn::build_host_multi(n_samples, offset, prefix_len, resp_ptr, resp_len, total_tokens, tile_q, tile_k,
+                                    bwd_tile_q, bwd_tile_k, out);
 }
 
 int psattn_meta_tiles(const psattn_meta* meta, int32_t grid, int32_t* tile_q, int32_t* tile_k,

@@ -20,7 +20,7 @@ from dataclasses import dataclass, field
 import numpy as np
 
 __all__ = [
-    "Workload", "CONFIGS", "make_workload", "make_tensors", "paired_workload",
+    "Workload", "CONFIGS", "make_workload", "make_tensors", "paired_workload", "with_layout",
     "custom_workload", "bf16_round", "to_bf16_bits", "from_bf16_bits",
 ]
 
@@ -168,6 +168,19 @@ def custom_workload(samples, *, offsets=None, total_tokens=None, hq=1, hkv=1, d=
                     total_tokens=int(total_tokens), offset=_i32(offsets), prefix_len=_i32(P),
                     chosen_len=_i32(C), rejected_len=_i32(R), seed=seed,
                     scale=float(1.0 / np.sqrt(d)) if scale is None else float(scale))
+
+
+def with_layout(w: Workload, offset, order, total_tokens, name=None) -> Workload:
+    """The same samples at other positions: `offset[i]` is the new flat start of sample i
+    (negative = sample left out) and `order` lists the samples by increasing offset, as a
+    packer returns them.  Only re-lays the table; the positions come from the caller."""
+    offset = np.asarray(offset)
+    order = np.asarray([i for i in np.asarray(order) if offset[i] >= 0], dtype=np.int64)
+    return Workload(name=name or (w.name + "-relaid"), dtype=w.dtype, n_q_heads=w.n_q_heads,
+                    n_kv_heads=w.n_kv_heads, head_dim=w.head_dim, total_tokens=int(total_tokens),
+                    offset=_i32(offset[order]), prefix_len=_i32(w.prefix_len[order]),
+                    chosen_len=_i32(w.chosen_len[order]), rejected_len=_i32(w.rejected_len[order]),
+                    seed=w.seed, row_len=w.row_len, scale=w.scale)
 
 
 def to_bf16_bits(x: np.ndarray) -> np.ndarray:

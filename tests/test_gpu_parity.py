@@ -256,6 +256,63 @@ def test_bf16_packed_rows_random():
     compare_full(w, tens, out, "bf16")
 
 
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64)])
+def test_multi_response_samples(dtype, d):
+    """Samples with 0, 1, 3 and 5 responses per prompt (psattn_build_meta_multi) through the same
+    forward and backward kernels, against the oracle's branch mask; several default tiles long."""
+    import torch
+    from gpu_util import to_dev, to_np
+    off, P = [5, 420, 900, 1000], [150, 64, 20, 33]
+    ptr, rl = [0, 3, 8, 9, 9], [60, 33, 129, 40, 70, 1, 64, 100, 77]
+    T, hq, hkv = 1060, 4, 2
+    rng = np.random.default_rng(181)
+    tens = {}
+    for n, h in (("Q", hq), ("K", hkv), ("V", hkv), ("dO", hq)):
+        x = rng.standard_normal((T, h, d), dtype=np.float32)
+        tens[n] = W.bf16_round(x) if dtype == "bf16" else x
+    scale = 1.0 / np.sqrt(d)
+    meta = ps.psattn_build_meta_multi(off, P, ptr, rl, T)
+    Q, K, V, dO = (to_dev(tens[n], dtype) for n in ("Q", "K", "V", "dO"))
+    O = torch.full_like(Q, float("nan"))
+    LSE = torch.full((hq, T), float("nan"), dtype=torch.float32, device="cuda")
+    ps.psattn_fwd(meta, Q, K, V, scale, O=O, LSE=LSE)
+    dQ, dK, dV = (torch.full_like(x, float("nan")) for x in (Q, K, V))
+    ps.psattn_bwd(meta, Q, K, V, O, dO, LSE, scale, dQ=dQ, dK=dK, dV=dV)
+    torch.cuda.synchronize()
+    out = dict(O=to_np(O), LSE=to_np(LSE), dQ=to_np(dQ), dK=to_np(dK), dV=to_np(dV))
+    D, B = orc.branch_arrays(off, P, ptr, rl, T)
+    ref = orc.backward(tens["Q"], tens["K"], tens["V"], tens["dO"], scale, None, None, D,
+                       mask=lambda *a: orc.dense_branch_mask(D, B, *a))
+    check_padding_zero(out, D)
+    real = D != orc.PAD_DOC
+    if dtype == "f32":
+        for name in ("O", "dQ", "dK", "dV"):
+            assert np.abs(out[name] - ref[name]).max() <= F32_TOL, name
+        assert np.abs(out["LSE"][:, real] - ref["LSE"][:, real]).max() <= F32_TOL
+    else:
+        assert meta.uses_mfma(ps.BF16, d, scale, backward=True)
+        check_o(out["O"], ref["O"], "multi-response")
+        assert np.abs(out["LSE"][:, real] - ref["LSE"][:, real]).max() <= BF16_LSE_TOL
+        check_grad(out["dQ"], ref["dQ"], "dQ", "multi-response", dq_delta_floor(tens["dO"], ref["O"], tens["K"], scale))
+        for name in ("dK", "dV"):
+            check_grad(out[name], ref[name], name, "multi-response")
+
+
+def test_bf16_ffd_packed_rows():
+    """Samples placed by the library's First-Fit-Decreasing packer (Section 4.3.2), rows padded to
+    the packing length: forward and backward on that layout against the oracle."""
+    rng = np.random.default_rng(171)
+    samples = [tuple(int(x) for x in rng.integers(5, 140, 3)) for _ in range(14)]
+    w0 = W.custom_workload(samples, hq=4, hkv=2, d=128, dtype="bf16", seed=172)
+    w0.row_len = 640
+    pk = ps.psattn_pack_ffd(w0.prefix_len, w0.chosen_len, w0.rejected_len, w0.row_len)
+    assert pk["n_rows"] >= 2 and pk["padding_tokens"] > 0
+    w = W.with_layout(w0, pk["offset"], pk["order"], pk["n_rows"] * w0.row_len)
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    compare_full(w, tens, out, "bf16", what="ffd packed rows")
+
+
 def test_bf16_long_sample_tile_lists_beyond_two_batches():
     """One sample of 9 200 tokens: tile lists of up to 144 entries, so the kernels' 64-entry
     list windows are refilled twice (the five configurations stop at 128 entries); two q-heads
