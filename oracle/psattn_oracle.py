@@ -17,7 +17,9 @@ What it follows:
   * the per-mini-batch block mask of Section 3.1 (blocks with no allowed pair are
     skipped), as a brute-force classification over the dense boolean mask;
   * First-Fit-Decreasing packing of whole samples into fixed-length rows
-    (Section 4.3.2), as the textbook loop.
+    (Section 4.3.2), as the textbook loop;
+  * rotary position embedding with the position ids of Section 3.1 (every
+    response restarts right behind the prompt, as in the paired format).
 
 Readings where the paper is silent (all restated where they are used):
   - start indices are row-absolute positions (they are compared with q and kv);
@@ -38,7 +40,10 @@ differences, the no-contamination invariant against plain causal attention on
 [prompt|chosen] and [prompt|rejected], packing independence, response swap
 symmetry, GQA expansion; for the packer a hand-worked example, the first-fit
 property checked by replay, and the 11/9 OPT + 6/9 bound against a brute-force
-optimum.  No function here is unpinned.
+optimum; for the rotary embedding explicit 2x2 rotation matrices, the
+relative-position property, finite differences, and equality with plain causal
+attention over [prompt | response] with ordinary positions.  No function here is
+unpinned.
 """
 from __future__ import annotations
 
@@ -465,3 +470,65 @@ def ffd_pack(lengths, row_len, max_rows=0):
             offset[i] = len(fill) * row_len
             fill.append(need)
     return np.asarray(offset, dtype=np.int32), len(fill)
+
+
+# --------------------------------------------------------------------------
+# rotary position embedding with the position ids of the paired format
+# (Section 3.1: position ids are set so that each response sits where it would
+# sit in the normal paired format, i.e. every response restarts right behind the
+# prompt)
+# --------------------------------------------------------------------------
+def position_ids(D, B):
+    """Position id of every token from its sample id D and branch id B (branch_arrays;
+    for the paper's two responses B = 1 is chosen, B = 2 rejected): prompt tokens count
+    from 0, the tokens of EVERY response count on from the prompt's length.  Padding: 0."""
+    T = D.shape[0]
+    pos = np.zeros(T, dtype=np.int64)
+    prompt_len, seen = {}, {}
+    for t in range(T):
+        d, b = int(D[t]), int(B[t])
+        if d == PAD_DOC:
+            continue
+        if b == 0:
+            pos[t] = prompt_len.get(d, 0)
+            prompt_len[d] = prompt_len.get(d, 0) + 1
+        else:
+            pos[t] = prompt_len.get(d, 0) + seen.get((d, b), 0)
+            seen[(d, b)] = seen.get((d, b), 0) + 1
+    return pos
+
+
+def rope_angles(pos, head_dim, theta):
+    """angle[t, i] = pos[t] * theta^(-2 i / head_dim), i = 0 .. head_dim/2 - 1."""
+    i = np.arange(head_dim // 2, dtype=np.float64)
+    return np.asarray(pos, dtype=np.float64)[:, None] * theta ** (-2.0 * i / head_dim)[None, :]
+
+
+def rope_rotate(x, pos, theta, inverse=False):
+    """Rotary embedding of x [T, H, d] (fp64): dimension i is paired with i + d/2 and the pair
+    is turned by angle[t, i] (by -angle with inverse=True, which is also the map that takes a
+    gradient w.r.t. the rotated tensor to the gradient w.r.t. the unrotated one)."""
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    ang = rope_angles(pos, d, theta)
+    if inverse:
+        ang = -ang
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    x1, x2 = x[..., :d // 2], x[..., d // 2:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def backward_rope(Q, K, V, dO, scale, theta, D, B, mask, heads=None, samples=None, round_operands=None):
+    """Attention with rotary embedding applied to Q and K first, forward and backward.
+    `round_operands(x)`, if given, is applied to the rotated Q and K before the attention
+    (a bf16 model stores the rotated activations in bf16).  dQ and dK are gradients w.r.t.
+    the UNROTATED Q and K.  Also returns the rotated operands Qr, Kr."""
+    pos = position_ids(D, B)
+    Qr, Kr = rope_rotate(Q, pos, theta), rope_rotate(K, pos, theta)
+    if round_operands is not None:
+        Qr, Kr = round_operands(Qr), round_operands(Kr)
+    out = backward(Qr, Kr, V, dO, scale, None, None, D, heads=heads, samples=samples, mask=mask)
+    out["dQ"] = rope_rotate(out["dQ"], pos, theta, inverse=True)
+    out["dK"] = rope_rotate(out["dK"], pos, theta, inverse=True)
+    out["Qr"], out["Kr"], out["pos"] = Qr, Kr, pos
+    return out
