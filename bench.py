@@ -86,10 +86,23 @@ class Runner:
     def step(self):
         ps, w = self.ps, self.w
         meta = self.build_meta()
-        ps.psattn_fwd(meta, self.Q, self.K, self.V, w.scale, O=self.O, LSE=self.LSE)
-        ps.psattn_bwd(meta, self.Q, self.K, self.V, self.O, self.dO, self.LSE, w.scale, dQ=self.dQ,
-                      dK=self.dK, dV=self.dV, workspace=self.ws)
+        if getattr(self, "rope", None) is not None:
+            ps.psattn_fwd_rope(meta, self.rope, self.Q, self.K, self.V, w.scale, O=self.O, LSE=self.LSE, Qr=self.Qr,
+                               Kr=self.Kr)
+            ps.psattn_bwd_rope(meta, self.rope, self.Qr, self.Kr, self.V, self.O, self.dO, self.LSE, w.scale,
+                               dQ=self.dQ, dK=self.dK, dV=self.dV, workspace=self.ws)
+        else:
+            ps.psattn_fwd(meta, self.Q, self.K, self.V, w.scale, O=self.O, LSE=self.LSE)
+            ps.psattn_bwd(meta, self.Q, self.K, self.V, self.O, self.dO, self.LSE, w.scale, dQ=self.dQ,
+                          dK=self.dK, dV=self.dV, workspace=self.ws)
         meta.free_async()
+
+    def enable_rope(self, theta=500000.0):
+        """Switch step() to the entry points that apply the rotary embedding inside the op."""
+        meta = self.build_meta()
+        self.rope = self.ps.Rope(self.w.head_dim, theta, meta.positions()[1])
+        meta.free()
+        self.Qr, self.Kr = self.torch.empty_like(self.Q), self.torch.empty_like(self.K)
 
     def build_meta_ms(self, n=20):
         """Host wall time of psattn_build_meta alone (sample table -> block mask -> upload enqueued)."""
@@ -388,6 +401,18 @@ def main():
             del rf
             torch.cuda.empty_cache()
         out["ffd_packing"] = ffd
+        # rotary embedding with the position ids of the paired format applied inside the op (Section 3.1):
+        # whole step with it against the step without it, next to what a separate elementwise RoPE pass
+        # over Q and K (read + write, forward; the same again for dQ, dK in the backward) would move
+        run.enable_rope()
+        ms_r, pp_r, pst_r = run.timed(max(5, min(args.steps, 20)), 3)
+        e = 2
+        sep_bytes = 2 * 2 * w.total_tokens * (w.n_q_heads + w.n_kv_heads) * w.head_dim * e
+        out["rope_fused"] = dict(workload=args.workload, ms_per_step=round(ms_r, 4), ms_per_step_without=round(ms_step, 4),
+                                 overhead_ms=round(ms_r - ms_step, 4),
+                                 ms_fwd=round(pp_r[0], 4), ms_dq=round(pp_r[2], 4), ms_dkdv=round(pp_r[3], 4),
+                                 separate_pass_bytes=sep_bytes,
+                                 separate_pass_ms_at_hbm_peak=round(sep_bytes / (PEAK_HBM_GBS * 1e9) * 1e3, 4))
         out["paper_context"] = "paper reports 1.1-1.5x (1.3-1.6x packed) end-to-end training speedup on 8xH100"
 
     if not args.no_cpu:

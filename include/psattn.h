@@ -53,6 +53,7 @@ extern "C" {
 #endif
 
 typedef struct psattn_meta psattn_meta; /* opaque */
+typedef struct psattn_rope psattn_rope; /* opaque: rotary-embedding table on one device */
 
 typedef enum {
     PSATTN_OK = 0,
@@ -276,6 +277,48 @@ int psattn_uses_mfma(const psattn_meta* meta, int32_t dt, int32_t head_dim, floa
  */
 int psattn_profile_enable(int32_t on);
 int psattn_profile_read(double* sum_ms, int64_t* count);
+
+/*
+ * Rotary position embedding inside the attention op, with the position ids of Section 3.1:
+ * every response restarts right behind the prompt, so that each response sees the positions
+ * it would have in the normal paired format (prompt tokens 0 .. p-1, the tokens of every
+ * response p, p+1, ...; with psattn_build_meta_multi likewise for each of the k responses).
+ * Convention: head dim i < head_dim/2 is paired with i + head_dim/2 and the pair is turned by
+ * position * theta^(-2i/head_dim) ("rotate-half"); the result is rounded to bfloat16 like any
+ * stored activation.  PSATTN_BF16 with head_dim 128 on the default tile grids only
+ * (PSATTN_EUNSUPPORTED otherwise).
+ *
+ * psattn_rope_create builds the cos/sin table for positions [0, max_positions) on the current
+ * device (host computes it in double precision; the call allocates device memory and waits
+ * for its upload: create it once, not per step).  A meta object that needs more positions
+ * than the table holds is refused with PSATTN_ELIMIT.
+ *
+ * psattn_fwd_rope: Q and K arrive UNROTATED.  K is rotated once into Kr (device
+ * [T, n_kv_heads, 128], caller-owned), Q is rotated in registers as the forward loads it
+ * and saved into Qr (device [T, n_q_heads, 128], caller-owned; NULL if no backward will
+ * follow).  O and LSE as for psattn_fwd.  psattn_rope_k is the K half alone.
+ *
+ * psattn_bwd_rope: takes the forward's Qr and Kr; dQ and dK are the gradients with respect to
+ * the UNROTATED Q and K (turned back in registers before they are stored), dV as usual.
+ * Workspace as for psattn_bwd.
+ *
+ * psattn_meta_copy_positions: host read-back of the position id of every token (0 for
+ * padding) and of the number of positions the object needs.
+ */
+int psattn_rope_create(int32_t head_dim, float theta, int32_t max_positions, void* hip_stream, psattn_rope** out);
+int psattn_rope_free(psattn_rope* rope);
+int psattn_rope_k(const psattn_meta* meta, const psattn_rope* rope, int32_t dt, int32_t n_kv_heads, int32_t head_dim,
+                  const void* K, void* Kr, void* hip_stream);
+int psattn_fwd_rope(const psattn_meta* meta, const psattn_rope* rope, int32_t dt, int32_t n_q_heads,
+                    int32_t n_kv_heads, int32_t head_dim, float scale,
+                    const void* Q, const void* K, const void* V, void* O, float* LSE,
+                    void* Qr, void* Kr, void* hip_stream);
+int psattn_bwd_rope(const psattn_meta* meta, const psattn_rope* rope, int32_t dt, int32_t n_q_heads,
+                    int32_t n_kv_heads, int32_t head_dim, float scale,
+                    const void* Qr, const void* Kr, const void* V, const void* O, const void* dO,
+                    const float* LSE, void* dQ, void* dK, void* dV,
+                    void* workspace, size_t workspace_bytes, void* hip_stream);
+int psattn_meta_copy_positions(const psattn_meta* meta, int32_t* pos /* host [T] */, int32_t* n_positions);
 
 /*
  * Measurement aid (no part of the computation): issues the memory operations that a

@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     GRID_BWD, GRID_FWD, TILE_FULL, TILE_PARTIAL, TILE_SKIPPED, Meta, PsattnError, lib_path,
     load_library, psattn_build_meta, psattn_bwd, psattn_bwd_workspace_bytes, psattn_fwd,
     psattn_kernel_name, psattn_profile_enable, psattn_profile_read, psattn_trim_pool, BF16, F32,
-    psattn_bwd_static, psattn_bwd_static_max_rows, psattn_probe_dq_atomics, psattn_pack_ffd, psattn_build_meta_multi,
+    psattn_bwd_static, psattn_bwd_static_max_rows, psattn_probe_dq_atomics, psattn_pack_ffd, psattn_build_meta_multi, Rope, psattn_fwd_rope, psattn_bwd_rope,
 )

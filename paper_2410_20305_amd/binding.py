@@ -21,6 +21,8 @@ EXPORTS = [
     "psattn_free_meta_async", "psattn_trim_pool", "psattn_uses_mfma",
     "psattn_bwd_static", "psattn_bwd_static_max_rows", "psattn_probe_dq_atomics",
     "psattn_pack_ffd", "psattn_build_meta_multi", "psattn_build_meta_multi_host",
+    "psattn_rope_create", "psattn_rope_free", "psattn_rope_k", "psattn_fwd_rope", "psattn_bwd_rope",
+    "psattn_meta_copy_positions",
 ]
 
 
@@ -50,6 +52,13 @@ def load_library():
     lib.psattn_build_meta_host.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp)]
     lib.psattn_build_meta_multi.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, vp, C.POINTER(vp)]
     lib.psattn_build_meta_multi_host.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, C.POINTER(vp)]
+    lib.psattn_rope_create.argtypes = [i32, f32, i32, vp, C.POINTER(vp)]
+    lib.psattn_rope_free.argtypes = [vp]
+    lib.psattn_rope_k.argtypes = [vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.psattn_fwd_rope.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.psattn_bwd_rope.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                    C.c_size_t, vp]
+    lib.psattn_meta_copy_positions.argtypes = [vp, vp, pi32]
     lib.psattn_free_meta.argtypes = [vp]
     lib.psattn_free_meta_async.argtypes = [vp, vp]
     lib.psattn_trim_pool.argtypes = []
@@ -179,6 +188,14 @@ class Meta:
         out = np.zeros(max(1, self.total_tokens), dtype=np.int32)
         _check(lib.psattn_meta_copy_key_desc(self.handle, out.ctypes.data), "psattn_meta_copy_key_desc")
         return out[:self.total_tokens]
+
+    def positions(self):
+        """(position id of every token, number of positions needed)."""
+        lib = load_library()
+        out = np.zeros(max(1, self.total_tokens), dtype=np.int32)
+        n = C.c_int32()
+        _check(lib.psattn_meta_copy_positions(self.handle, out.ctypes.data, C.byref(n)), "psattn_meta_copy_positions")
+        return out[:self.total_tokens], n.value
 
     def allowed_pairs(self):
         lib = load_library()
@@ -343,6 +360,85 @@ def psattn_bwd_static(meta: Meta, Q, K, V, O, dO, LSE, scale, dQ, dK, dV, stream
 
 def psattn_bwd_static_max_rows() -> int:
     return int(load_library().psattn_bwd_static_max_rows())
+
+
+class Rope:
+    """Owner of a psattn_rope handle (cos/sin table on the current device)."""
+
+    def __init__(self, head_dim, theta, max_positions, stream=None):
+        lib = load_library()
+        h = C.c_void_p()
+        _check(lib.psattn_rope_create(int(head_dim), float(theta), int(max_positions), _stream_ptr(stream), C.byref(h)),
+               "psattn_rope_create")
+        self._h = h
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("rope table already freed")
+        return self._h
+
+    def free(self):
+        if self._h is not None:
+            _check(load_library().psattn_rope_free(self._h), "psattn_rope_free")
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def psattn_fwd_rope(meta: Meta, rope: Rope, Q, K, V, scale, O=None, LSE=None, Qr=None, Kr=None, stream=None):
+    """O, LSE, Qr, Kr = forward with rotary embedding applied to the unrotated Q, K inside the op."""
+    import torch
+    lib = load_library()
+    T, Hq, d = Q.shape
+    Hkv = K.shape[1]
+    _check_tensor(Q, "Q", (meta.total_tokens, Hq, d), None)
+    _check_tensor(K, "K", (T, Hkv, d), Q.dtype)
+    _check_tensor(V, "V", (T, Hkv, d), Q.dtype)
+    O = torch.empty_like(Q) if O is None else O
+    LSE = torch.empty((Hq, T), dtype=torch.float32, device=Q.device) if LSE is None else LSE
+    Qr = torch.empty_like(Q) if Qr is None else Qr
+    Kr = torch.empty_like(K) if Kr is None else Kr
+    _check_tensor(O, "O", Q.shape, Q.dtype)
+    _check_tensor(LSE, "LSE", (Hq, T), torch.float32)
+    _check_tensor(Qr, "Qr", Q.shape, Q.dtype)
+    _check_tensor(Kr, "Kr", K.shape, Q.dtype)
+    st = lib.psattn_fwd_rope(meta.handle, rope.handle, _dtype_code(Q), Hq, Hkv, d, float(scale), Q.data_ptr(),
+                             K.data_ptr(), V.data_ptr(), O.data_ptr(), LSE.data_ptr(), Qr.data_ptr(), Kr.data_ptr(),
+                             _stream_ptr(stream))
+    _check(st, "psattn_fwd_rope")
+    return O, LSE, Qr, Kr
+
+
+def psattn_bwd_rope(meta: Meta, rope: Rope, Qr, Kr, V, O, dO, LSE, scale, dQ=None, dK=None, dV=None, workspace=None,
+                    stream=None):
+    """dQ, dK, dV (w.r.t. the unrotated Q, K) from the forward's rotated Qr, Kr."""
+    import torch
+    lib = load_library()
+    T, Hq, d = Qr.shape
+    Hkv = Kr.shape[1]
+    _check_tensor(Qr, "Qr", (meta.total_tokens, Hq, d), None)
+    for t, name, shape in ((Kr, "Kr", (T, Hkv, d)), (V, "V", (T, Hkv, d)), (O, "O", Qr.shape), (dO, "dO", Qr.shape)):
+        _check_tensor(t, name, shape, Qr.dtype)
+    _check_tensor(LSE, "LSE", (Hq, T), torch.float32)
+    dQ = torch.empty_like(Qr) if dQ is None else dQ
+    dK = torch.empty_like(Kr) if dK is None else dK
+    dV = torch.empty_like(V) if dV is None else dV
+    for t, name, shape in ((dQ, "dQ", Qr.shape), (dK, "dK", Kr.shape), (dV, "dV", Kr.shape)):
+        _check_tensor(t, name, shape, Qr.dtype)
+    need = psattn_bwd_workspace_bytes(meta, Hq, Hkv, d)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=Qr.device)
+    st = lib.psattn_bwd_rope(meta.handle, rope.handle, _dtype_code(Qr), Hq, Hkv, d, float(scale), Qr.data_ptr(),
+                             Kr.data_ptr(), V.data_ptr(), O.data_ptr(), dO.data_ptr(), LSE.data_ptr(), dQ.data_ptr(),
+                             dK.data_ptr(), dV.data_ptr(), workspace.data_ptr(),
+                             workspace.numel() * workspace.element_size(), _stream_ptr(stream))
+    _check(st, "psattn_bwd_rope")
+    return dQ, dK, dV
 
 
 def psattn_probe_dq_atomics(meta: Meta, n_q_heads, n_kv_heads, acc, mode, stream=None) -> None:

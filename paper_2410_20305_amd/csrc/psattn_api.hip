@@ -252,7 +252,7 @@ size_t bwd_scratch_bytes(const psattn_meta* meta, int32_t n_q_heads) {
 int bwd_checked(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                 float scale, const void* Q, const void* K, const void* V, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, void* scratch_base, size_t scratch_bytes,
-                void* hip_stream) {
+                void* hip_stream, const float* rope_table) {
     const int rc = check_common(meta, dt, n_q_heads, n_kv_heads, head_dim);
     if (rc != PSATTN_OK) return rc;
     if (meta->T == 0) return PSATTN_OK;
@@ -263,10 +263,12 @@ int bwd_checked(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t 
     a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = scale;
     a.Q = Q; a.K = K; a.V = V; a.O = O; a.dO = dO; a.LSE = LSE;
     a.dQ = dQ; a.dK = dK; a.dV = dV;
+    a.rope = rope_table;
     a.delta = reinterpret_cast<float*>(align_up(reinterpret_cast<uintptr_t>(scratch_base), 256));
     a.lse2 = a.delta + align_up(sizeof(float) * static_cast<size_t>(meta->T) * n_q_heads, 256) / sizeof(float);
     int err = 0;
     const bool mfma = mfma_bwd_ok(meta, dt, head_dim, scale);
+    if (rope_table && !mfma) return PSATTN_EUNSUPPORTED;  // rotary embedding lives in the matrix-core kernels only
     if (!mfma) {  // the MFMA dQ kernel computes delta itself and leaves it in the scratch
         PassTimer t(1, hip_stream);
         err = launch_delta(dt, a, hip_stream);
@@ -283,6 +285,29 @@ int bwd_checked(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t 
         PassTimer t(3, hip_stream);
         err = mfma ? launch_mfma_dkdv(a, hip_stream) : launch_generic_dkdv(dt, a, hip_stream);
         g_last_kernel[3] = mfma ? "psattn_dkdv_bf16_mfma" : "generic_dkdv";
+    }
+    return err == 0 ? PSATTN_OK : PSATTN_EHIP;
+}
+
+int fwd_checked(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                float scale, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                const float* rope_table, void* Qr, void* hip_stream) {
+    int rc = check_common(meta, dt, n_q_heads, n_kv_heads, head_dim);
+    if (rc != PSATTN_OK) return rc;
+    if (meta->T == 0) return PSATTN_OK;
+    if (!Q || !K || !V || !O || !LSE) return PSATTN_EINVAL;
+    AttnArgs a{};
+    a.meta = meta->dev;
+    a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = scale;
+    a.Q = Q; a.K = K; a.V = V; a.Oout = O; a.LSEout = LSE;
+    a.rope = rope_table; a.Qr = Qr;
+    const bool mfma = mfma_fwd_ok(meta, dt, head_dim, scale);
+    if (rope_table && !mfma) return PSATTN_EUNSUPPORTED;  // rotary embedding lives in the matrix-core kernels only
+    int err;
+    {
+        PassTimer t(0, hip_stream);
+        err = mfma ? launch_mfma_fwd(a, hip_stream) : launch_generic_fwd(dt, a, hip_stream);
+        g_last_kernel[0] = mfma ? "psattn_fwd_bf16_mfma" : "generic_fwd";
     }
     return err == 0 ? PSATTN_OK : PSATTN_EHIP;
 }
@@ -377,22 +402,7 @@ int psattn_uses_mfma(const psattn_meta* meta, int32_t dt, int32_t head_dim, floa
 int psattn_fwd(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads,
                int32_t head_dim, float scale, const void* Q, const void* K, const void* V, void* O,
                float* LSE, void* hip_stream) {
-    int rc = check_common(meta, dt, n_q_heads, n_kv_heads, head_dim);
-    if (rc != PSATTN_OK) return rc;
-    if (meta->T == 0) return PSATTN_OK;
-    if (!Q || !K || !V || !O || !LSE) return PSATTN_EINVAL;
-    AttnArgs a{};
-    a.meta = meta->dev;
-    a.Hq = n_q_heads; a.Hkv = n_kv_heads; a.d = head_dim; a.scale = scale;
-    a.Q = Q; a.K = K; a.V = V; a.Oout = O; a.LSEout = LSE;
-    int err;
-    {
-        PassTimer t(0, hip_stream);
-        const bool mfma = mfma_fwd_ok(meta, dt, head_dim, scale);
-        err = mfma ? launch_mfma_fwd(a, hip_stream) : launch_generic_fwd(dt, a, hip_stream);
-        g_last_kernel[0] = mfma ? "psattn_fwd_bf16_mfma" : "generic_fwd";
-    }
-    return err == 0 ? PSATTN_OK : PSATTN_EHIP;
+    return fwd_checked(meta, dt, n_q_heads, n_kv_heads, head_dim, scale, Q, K, V, O, LSE, nullptr, nullptr, hip_stream);
 }
 
 size_t psattn_bwd_workspace_bytes(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads,

@@ -65,6 +65,7 @@ struct psattn_meta {
     int32_t T = 0;
     int32_t n_samples = 0;
     int64_t n_allowed = 0;
+    int32_t n_positions = 0;        // 1 + the largest position id of any token (prompt length + longest response)
     std::vector<int32_t> tok_desc;  // [3T]  (s, hole_lo, hole_hi)
     std::vector<int32_t> key_hi;    // [T]   queries that may read key j are [j, key_hi[j])
     psattn::TileCsr fwd, bwd;
@@ -100,9 +101,19 @@ struct AttnArgs {
     const float* LSE;
     void *Oout, *dQ, *dK, *dV;
     float* LSEout;
+    // Rotary embedding (nullptr = none): table [positions][128] = cos[64] | sin[64] per position id.
+    // Forward: Q arrives unrotated, is rotated in registers and, if Qr is set, saved rotated for the
+    // backward; K arrives rotated.  Backward: Q and K arrive rotated, dQ and dK leave unrotated.
+    const float* rope;
+    void* Qr;
     float* delta;  // [Hq, T]  workspace: rowsum(dO o O); the MFMA kernels keep its negative here
     float* lse2;   // [Hq, T]  workspace: LSE * log2(e), written by the MFMA dQ pass for the dK/dV pass
 };
+
+// psattn_fwd with optional rotary embedding (rope_table == nullptr: none).
+int fwd_checked(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
+                float scale, const void* Q, const void* K, const void* V, void* O, float* LSE,
+                const float* rope_table, void* Qr, void* hip_stream);
 
 // psattn_bwd without the workspace-size lookup: argument checks, then delta / dQ / dK/dV
 // on `scratch_base` (device memory of at least bwd_scratch_bytes()).  Returns a psattn_status.
@@ -110,7 +121,7 @@ size_t bwd_scratch_bytes(const psattn_meta* meta, int32_t n_q_heads);
 int bwd_checked(const psattn_meta* meta, int32_t dt, int32_t n_q_heads, int32_t n_kv_heads, int32_t head_dim,
                 float scale, const void* Q, const void* K, const void* V, const void* O, const void* dO,
                 const float* LSE, void* dQ, void* dK, void* dV, void* scratch_base, size_t scratch_bytes,
-                void* hip_stream);
+                void* hip_stream, const float* rope_table = nullptr);
 
 // Launchers (each returns a hipError_t cast to int; 0 = success).
 int launch_generic_fwd(int dt, const AttnArgs& a, void* stream);

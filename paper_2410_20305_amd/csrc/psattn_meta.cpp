@@ -168,7 +168,7 @@ int build_host_multi(int32_t n_samples, const int32_t* offset, const int32_t* pr
         if ((T + t - 1) / t >= kMaxTiles) return PSATTN_EUNSUPPORTED;
     std::vector<Sample> samples;
     std::vector<int64_t> starts;  // response boundaries of all samples, k + 1 per sample
-    int64_t prev_end = 0, n_allowed = 0;
+    int64_t prev_end = 0, n_allowed = 0, n_positions = 0;
     try {
         samples.reserve(n_samples);
         if (n_samples > 0) {
@@ -193,8 +193,10 @@ int build_host_multi(int32_t n_samples, const int32_t* offset, const int32_t* pr
                 t += r;
                 if (t > T) return PSATTN_ERANGE;
                 n_allowed += r * p + tri(r);
+                n_positions = std::max(n_positions, p + r);  // every response counts on from the prompt's length
                 starts.push_back(t);
             }
+            n_positions = std::max(n_positions, p);
             if (t == o) return PSATTN_EINVAL;  // empty sample
             if (t > T) return PSATTN_ERANGE;
             samples.push_back({o, o + p, t, nullptr, resp_ptr[i + 1] - resp_ptr[i]});
@@ -205,6 +207,7 @@ int build_host_multi(int32_t n_samples, const int32_t* offset, const int32_t* pr
         m->T = total_tokens;
         m->n_samples = n_samples;
         m->n_allowed = n_allowed;
+        m->n_positions = static_cast<int32_t>(n_positions);
         m->tok_desc.assign(static_cast<size_t>(3) * T, 0);
         m->key_hi.assign(T, 0);
         for (int64_t t = 0; t < T; ++t) m->tok_desc[3 * t] = kPadStart;
@@ -315,6 +318,18 @@ int psattn_meta_copy_tok_desc(const psattn_meta* meta, int32_t* tok_desc) {
 int psattn_meta_copy_key_desc(const psattn_meta* meta, int32_t* key_hi) {
     if (!meta || (!key_hi && meta->T > 0)) return PSATTN_EINVAL;
     if (meta->T > 0) std::memcpy(key_hi, meta->key_hi.data(), meta->key_hi.size() * sizeof(int32_t));
+    return PSATTN_OK;
+}
+
+int psattn_meta_copy_positions(const psattn_meta* meta, int32_t* pos, int32_t* n_positions) {
+    if (!meta || (!pos && meta->T > 0)) return PSATTN_EINVAL;
+    for (int32_t t = 0; t < meta->T; ++t) {
+        const int32_t s = meta->tok_desc[3 * t];
+        // the hidden key range lies between the prompt and the token's own response: skipping it
+        // puts the response right behind the prompt
+        pos[t] = s == psattn::kPadStart ? 0 : t - s - (meta->tok_desc[3 * t + 2] - meta->tok_desc[3 * t + 1]);
+    }
+    if (n_positions) *n_positions = meta->n_positions;
     return PSATTN_OK;
 }
 

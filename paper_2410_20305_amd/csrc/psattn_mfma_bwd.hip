@@ -191,6 +191,28 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
     if (it < n_ent) step(std::integral_constant<int, 0>{});
     // no copy may still be writing to LDS when the workgroup ends
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (a.rope) {
+        // Q arrived rotated: what was accumulated is the gradient w.r.t. the rotated query; turning
+        // it back by the same angles gives the gradient w.r.t. the unrotated one.  Accumulator
+        // element i of block db is head dim 32 db + 8 (i / 4) + 4 g + i % 4; its partner sits in
+        // block db + 2 at the same i.
+        const float* trow = a.rope + static_cast<size_t>(rope_position(tk, q_row)) * 128;
+#pragma unroll
+        for (int db = 0; db < 2; ++db)
+#pragma unroll
+            for (int i4 = 0; i4 < 4; ++i4) {
+                const float4 c = *reinterpret_cast<const float4*>(trow + 32 * db + 8 * i4 + 4 * g);
+                const float4 s = *reinterpret_cast<const float4*>(trow + 64 + 32 * db + 8 * i4 + 4 * g);
+                const float cs[4] = {c.x, c.y, c.z, c.w}, sn[4] = {s.x, s.y, s.z, s.w};
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    float lo = dq[db][4 * i4 + k], hi = dq[db + 2][4 * i4 + k];
+                    rope_turn<true>(lo, hi, cs[k], sn[k]);
+                    dq[db][4 * i4 + k] = lo;
+                    dq[db + 2][4 * i4 + k] = hi;
+                }
+            }
+    }
     if (valid) {
         uint16_t* row = static_cast<uint16_t*>(a.dQ) + qoff;
         const float sc = a.scale;

@@ -307,6 +307,46 @@ struct EntryStream {
     }
 };
 
+// ---- rotary position embedding (Section 3.1: position ids follow the paired format)
+// Dimension i < 64 is paired with i + 64 and the pair is turned by the angle of (position, i).
+// The table row of a position holds cos of the 64 angles, then sin.  All layouts in these kernels
+// keep both members of a pair in the same lane, so rotating is lane-local.
+
+// position id of token t: prompt and first response count on from the sample's start; a later
+// response skips the hidden range [hole_lo, hole_hi), which puts it right behind the prompt
+__device__ inline int rope_position(const Tok4& tk, int t) {
+    return tk.s == kPadStart ? 0 : t - tk.s - (tk.hole_hi - tk.hole_lo);
+}
+
+// (x1, x2) -> turned by +angle (inverse = false) or -angle (inverse = true)
+template <bool INVERSE>
+__device__ __forceinline__ void rope_turn(float& x1, float& x2, float c, float s) {
+    const float y1 = INVERSE ? fmaf(x2, s, x1 * c) : fmaf(-x2, s, x1 * c);
+    const float y2 = INVERSE ? fmaf(-x1, s, x2 * c) : fmaf(x1, s, x2 * c);
+    x1 = y1;
+    x2 = y2;
+}
+
+// Rotates 8 packed bf16 (dims i0 .. i0 + 7, i0 < 64) and their partners (dims 64 + i0 ..) in place;
+// `row` points at the table row of the token's position.
+__device__ inline void rope_frag8(Frag8& lo, Frag8& hi, const float* row, int i0) {
+    const float4 c0 = *reinterpret_cast<const float4*>(row + i0), c1 = *reinterpret_cast<const float4*>(row + i0 + 4);
+    const float4 s0 = *reinterpret_cast<const float4*>(row + 64 + i0), s1 = *reinterpret_cast<const float4*>(row + 64 + i0 + 4);
+    const float cs[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+    const float sn[8] = {s0.x, s0.y, s0.z, s0.w, s1.x, s1.y, s1.z, s1.w};
+    uint32_t lw[4] = {lo.u.x, lo.u.y, lo.u.z, lo.u.w}, hw[4] = {hi.u.x, hi.u.y, hi.u.z, hi.u.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        float a0 = __uint_as_float(lw[j] << 16), a1 = __uint_as_float(lw[j] & 0xffff0000u);
+        float b0 = __uint_as_float(hw[j] << 16), b1 = __uint_as_float(hw[j] & 0xffff0000u);
+        rope_turn<false>(a0, b0, cs[2 * j], sn[2 * j]);
+        rope_turn<false>(a1, b1, cs[2 * j + 1], sn[2 * j + 1]);
+        f32x2 va = {a0, a1}, vb = {b0, b1};
+        lo.p[j] = __builtin_convertvector(va, bf16x2);
+        hi.p[j] = __builtin_convertvector(vb, bf16x2);
+    }
+}
+
 __device__ inline void store4(uint16_t* dst, float a, float b, float c, float d) {
     f32x2 v0 = {a, b}, v1 = {c, d};
     union { bf16x2 p[2]; uint2 u; } o;

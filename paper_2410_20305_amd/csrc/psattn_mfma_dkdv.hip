@@ -321,11 +321,37 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
         static_for<0, 16>([&](auto Q4) {
             constexpr int q4 = decltype(Q4)::value, db = q4 >> 2, i4 = q4 & 3;
             const int d = 32 * db + 8 * i4 + 4 * g;
-            store4(krow + d, acc_get<kAccDK + 16 * db + 4 * i4 + 0>() * sc, acc_get<kAccDK + 16 * db + 4 * i4 + 1>() * sc,
-                   acc_get<kAccDK + 16 * db + 4 * i4 + 2>() * sc, acc_get<kAccDK + 16 * db + 4 * i4 + 3>() * sc);
             store4(vrow + d, acc_get<kAccDV + 16 * db + 4 * i4 + 0>(), acc_get<kAccDV + 16 * db + 4 * i4 + 1>(),
                    acc_get<kAccDV + 16 * db + 4 * i4 + 2>(), acc_get<kAccDV + 16 * db + 4 * i4 + 3>());
         });
+        if (a.rope) {
+            // K arrived rotated: turn dK back by the key's angles (accumulator element 4 i4 + k of block
+            // db is head dim 32 db + 8 i4 + 4 g + k; its partner sits in block db + 2)
+            const float* trow = a.rope + static_cast<size_t>(rope_position(a.meta.tok[key], key)) * 128;
+            static_for<0, 8>([&](auto Q4) {
+                constexpr int q4 = decltype(Q4)::value, db = q4 >> 2, i4 = q4 & 3;
+                const int d = 32 * db + 8 * i4 + 4 * g;
+                const float4 c = *reinterpret_cast<const float4*>(trow + d);
+                const float4 s = *reinterpret_cast<const float4*>(trow + 64 + d);
+                float l0 = acc_get<kAccDK + 16 * db + 4 * i4 + 0>(), l1 = acc_get<kAccDK + 16 * db + 4 * i4 + 1>(),
+                      l2 = acc_get<kAccDK + 16 * db + 4 * i4 + 2>(), l3 = acc_get<kAccDK + 16 * db + 4 * i4 + 3>();
+                float h0 = acc_get<kAccDK + 16 * (db + 2) + 4 * i4 + 0>(), h1 = acc_get<kAccDK + 16 * (db + 2) + 4 * i4 + 1>(),
+                      h2 = acc_get<kAccDK + 16 * (db + 2) + 4 * i4 + 2>(), h3 = acc_get<kAccDK + 16 * (db + 2) + 4 * i4 + 3>();
+                rope_turn<true>(l0, h0, c.x, s.x);
+                rope_turn<true>(l1, h1, c.y, s.y);
+                rope_turn<true>(l2, h2, c.z, s.z);
+                rope_turn<true>(l3, h3, c.w, s.w);
+                store4(krow + d, l0 * sc, l1 * sc, l2 * sc, l3 * sc);
+                store4(krow + 64 + d, h0 * sc, h1 * sc, h2 * sc, h3 * sc);
+            });
+        } else {
+            static_for<0, 16>([&](auto Q4) {
+                constexpr int q4 = decltype(Q4)::value, db = q4 >> 2, i4 = q4 & 3;
+                const int d = 32 * db + 8 * i4 + 4 * g;
+                store4(krow + d, acc_get<kAccDK + 16 * db + 4 * i4 + 0>() * sc, acc_get<kAccDK + 16 * db + 4 * i4 + 1>() * sc,
+                       acc_get<kAccDK + 16 * db + 4 * i4 + 2>() * sc, acc_get<kAccDK + 16 * db + 4 * i4 + 3>() * sc);
+            });
+        }
     }
 }
 

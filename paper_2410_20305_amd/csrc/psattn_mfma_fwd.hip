@@ -33,6 +33,18 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
         qf[t].u = valid ? *reinterpret_cast<const uint4*>(Q + (static_cast<size_t>(q_row) * Hq + h) * 128 + 16 * t + 8 * g)
                         : make_uint4(0, 0, 0, 0);
 
+    if (a.rope) {
+        // rotary embedding of this lane's query in registers; the rotated row is also saved for
+        // the backward, which streams Q tiles straight into LDS and cannot rotate them on the way
+        const float* row = a.rope + static_cast<size_t>(rope_position(tk, q_row)) * 128;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) rope_frag8(qf[t], qf[t + 4], row, 16 * t + 8 * g);
+        if (valid && a.Qr) {
+            uint16_t* qr = static_cast<uint16_t*>(a.Qr) + (static_cast<size_t>(q_row) * Hq + h) * 128;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) *reinterpret_cast<uint4*>(qr + 16 * t + 8 * g) = qf[t].u;
+        }
+    }
     f32x16 o[4];
 #pragma unroll
     for (int db = 0; db < 4; ++db)
