@@ -19,7 +19,9 @@ What it follows:
   * First-Fit-Decreasing packing of whole samples into fixed-length rows
     (Section 4.3.2), as the textbook loop;
   * rotary position embedding with the position ids of Section 3.1 (every
-    response restarts right behind the prompt, as in the paired format).
+    response restarts right behind the prompt, as in the paired format);
+  * the total log-probability of every response and the DPO loss of Eq. 1
+    (Section 2.1), with their gradients.
 
 Readings where the paper is silent (all restated where they are used):
   - start indices are row-absolute positions (they are compared with q and kv);
@@ -42,8 +44,9 @@ symmetry, GQA expansion; for the packer a hand-worked example, the first-fit
 property checked by replay, and the 11/9 OPT + 6/9 bound against a brute-force
 optimum; for the rotary embedding explicit 2x2 rotation matrices, the
 relative-position property, finite differences, and equality with plain causal
-attention over [prompt | response] with ordinary positions.  No function here is
-unpinned.
+attention over [prompt | response] with ordinary positions; for the
+log-probabilities torch's cross entropy over the paired format, a closed form
+for uniform logits and autograd.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -532,3 +535,77 @@ def backward_rope(Q, K, V, dO, scale, theta, D, B, mask, heads=None, samples=Non
     out["dK"] = rope_rotate(out["dK"], pos, theta, inverse=True)
     out["Qr"], out["Kr"], out["pos"] = Qr, Kr, pos
     return out
+
+
+# --------------------------------------------------------------------------
+# per-response log-probabilities and the DPO loss (Section 2.1, Eq. 1)
+# --------------------------------------------------------------------------
+# Eq. 1 needs log pi(y | x), the total log-probability of each completion.  In the
+# prefix-shared sequence the logits row of token t predicts the next token of t's own
+# branch: inside a response that is token t + 1; the LAST prompt token predicts the first
+# token of every response.  (Eq. 1 is printed with a ratio of the two log-probabilities; it
+# is read as DPO defines it, with the difference log pi_theta - log pi_ref, i.e. the log of
+# the ratio.)
+def prediction_items(offset, prefix_len, resp_ptr, resp_len):
+    """[(response index, logits row, position of the target token)] in response order.  A
+    response whose sample has an empty prompt has nothing to predict its first token from:
+    that token contributes nothing."""
+    items = []
+    for i in range(len(offset)):
+        o, p = int(offset[i]), int(prefix_len[i])
+        start = o + p
+        for j in range(int(resp_ptr[i]), int(resp_ptr[i + 1])):
+            n = int(resp_len[j])
+            for u in range(n):
+                if u == 0:
+                    if p > 0:
+                        items.append((j, o + p - 1, start))
+                else:
+                    items.append((j, start + u - 1, start + u))
+            start += n
+    return items
+
+
+def log_softmax_rows(logits):
+    x = np.asarray(logits, dtype=np.float64)
+    m = x.max(axis=-1, keepdims=True)
+    return x - m - np.log(np.exp(x - m).sum(axis=-1, keepdims=True))
+
+
+def response_logprobs(logits, token_ids, offset, prefix_len, resp_ptr, resp_len):
+    """log pi(response j | prompt) for every response: the sum over its tokens of the
+    log-softmax of the predicting row at that token's id.  logits [T, V], token_ids [T]."""
+    n_resp = int(resp_ptr[-1]) if len(resp_ptr) else 0
+    out = np.zeros(n_resp)
+    items = prediction_items(offset, prefix_len, resp_ptr, resp_len)
+    rows = sorted({r for _, r, _ in items})
+    ls = dict(zip(rows, log_softmax_rows(np.asarray(logits)[rows]))) if rows else {}
+    for j, row, tpos in items:
+        out[j] += ls[row][int(token_ids[tpos])]
+    return out
+
+
+def response_logprobs_grad(logits, token_ids, offset, prefix_len, resp_ptr, resp_len, d_logp):
+    """d(sum_j d_logp[j] * logp_j) / d logits, [T, V]: each item adds d_logp[j] * (onehot(target) -
+    softmax(row)) to its row; rows that predict nothing stay zero."""
+    x = np.asarray(logits, dtype=np.float64)
+    g = np.zeros_like(x)
+    for j, row, tpos in prediction_items(offset, prefix_len, resp_ptr, resp_len):
+        p = np.exp(log_softmax_rows(x[row:row + 1])[0])
+        g[row] -= d_logp[j] * p
+        g[row, int(token_ids[tpos])] += d_logp[j]
+    return g
+
+
+def dpo_loss(logp_policy, logp_ref, beta):
+    """Per-sample DPO loss for responses stored as (chosen, rejected) pairs:
+    -log sigmoid(beta * ((pc - rc) - (pr - rr))), and its derivative w.r.t. the policy
+    log-probabilities (same layout)."""
+    lp, lr = np.asarray(logp_policy, dtype=np.float64), np.asarray(logp_ref, dtype=np.float64)
+    z = beta * ((lp[0::2] - lr[0::2]) - (lp[1::2] - lr[1::2]))
+    loss = np.logaddexp(0.0, -z)                 # -log sigmoid(z)
+    dz = -1.0 / (1.0 + np.exp(z))                # d loss / d z = -sigmoid(-z)
+    d = np.zeros_like(lp)
+    d[0::2] = beta * dz
+    d[1::2] = -beta * dz
+    return loss, d
