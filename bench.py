@@ -415,6 +415,48 @@ def main():
                                  separate_pass_ms_at_hbm_peak=round(sep_bytes / (PEAK_HBM_GBS * 1e9) * 1e3, 4))
         out["paper_context"] = "paper reports 1.1-1.5x (1.3-1.6x packed) end-to-end training speedup on 8xH100"
 
+    if not args.no_extras:
+        # per-response log-probabilities + DPO loss + backward to the logits (Section 2.1, Eq. 1) on the same
+        # sample table, Mistral-7B vocabulary; all three passes stream logits rows: HBM roofline
+        V = 32000
+        ptr = 2 * np.arange(w.n_samples + 1, dtype=np.int32)
+        rl = np.stack([w.chosen_len, w.rejected_len], axis=1).reshape(-1).astype(np.int32)
+        plan = ps.LogprobPlan(w.offset, w.prefix_len, ptr, rl, w.total_tokens)
+        g = torch.Generator(device="cuda")
+        g.manual_seed(9)
+        logits = torch.randn((w.total_tokens, V), generator=g, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        ids = torch.randint(0, V, (w.total_tokens,), generator=g, device="cuda", dtype=torch.int32)
+        row_lse = torch.zeros(w.total_tokens, dtype=torch.float32, device="cuda")
+        logp = torch.empty(plan.n_responses, dtype=torch.float32, device="cuda")
+        dlogits = torch.empty_like(logits)
+        ref_lp = logp.clone()
+        t_f, t_b = [], []
+        for it in range(8):
+            a, b, c = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+            a.record()
+            ps.psattn_logprob_fwd(plan, logits, ids, row_lse, logp)
+            b.record()
+            _, dlp = ps.psattn_dpo_loss(logp, ref_lp if it else logp, 0.1)
+            ps.psattn_logprob_bwd(plan, logits, ids, row_lse, dlp, dlogits)
+            c.record()
+            torch.cuda.synchronize()
+            if it >= 2:
+                t_f.append(a.elapsed_time(b))
+                t_b.append(b.elapsed_time(c))
+        fb = plan.n_rows * V * 2
+        bb = plan.n_rows * V * 2 + w.total_tokens * V * 2
+        out["logprob_head"] = dict(workload=args.workload, vocab=V, dtype="bf16", predicting_rows=plan.n_rows,
+                                   buffer_rows=w.total_tokens, ms_fwd=round(float(np.median(t_f)), 4),
+                                   ms_loss_bwd=round(float(np.median(t_b)), 4),
+                                   fwd_GBs=round(fb / (float(np.median(t_f)) * 1e-3) / 1e9, 1),
+                                   bwd_GBs=round(bb / (float(np.median(t_b)) * 1e-3) / 1e9, 1),
+                                   roofline=dict(bound="hbm", kernel="psattn_lp_bwd", achieved=round(bb / (float(np.median(t_b)) * 1e-3) / 1e9, 1),
+                                                 peak=PEAK_HBM_GBS, unit="GB/s",
+                                                 frac=round(bb / (float(np.median(t_b)) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                                 traffic=None, algorithmic_bytes_per_launch=bb))
+        del logits, dlogits
+        torch.cuda.empty_cache()
+
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(w, tens)
     print(json.dumps(out))

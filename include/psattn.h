@@ -54,6 +54,7 @@ extern "C" {
 
 typedef struct psattn_meta psattn_meta; /* opaque */
 typedef struct psattn_rope psattn_rope; /* opaque: rotary-embedding table on one device */
+typedef struct psattn_lp_plan psattn_lp_plan; /* opaque: which logits rows predict which tokens */
 
 typedef enum {
     PSATTN_OK = 0,
@@ -319,6 +320,47 @@ int psattn_bwd_rope(const psattn_meta* meta, const psattn_rope* rope, int32_t dt
                     const float* LSE, void* dQ, void* dK, void* dV,
                     void* workspace, size_t workspace_bytes, void* hip_stream);
 int psattn_meta_copy_positions(const psattn_meta* meta, int32_t* pos /* host [T] */, int32_t* n_positions);
+
+/*
+ * Per-response log-probabilities and the DPO loss (Section 2.1, Eq. 1: the loss needs
+ * log pi(y | x), the total log-probability of each completion).  In the prefix-shared
+ * sequence the logits row of a token predicts the next token of the token's own branch:
+ * inside a response the following token; the LAST prompt token predicts the first token of
+ * every response.  Other prompt rows, the last row of every response and padding predict
+ * nothing and are never read.  A response behind an empty prompt has nothing to predict its
+ * first token from; that token contributes nothing.
+ *
+ * psattn_logprob_plan: from the sample table (host arrays, as for psattn_build_meta_multi;
+ * the paper's format is two responses per sample, chosen then rejected) builds the small
+ * device tables the passes need.  Allocates device memory and waits for its upload.
+ *
+ * psattn_logprob_fwd: logits device [T, vocab] (float or bfloat16 by dt), token_ids device
+ * int32 [T].  Writes row_lse[t] = log sum exp(logits[t, :]) for every row that predicts
+ * something (device float [T]; other entries untouched) and resp_logp[j] = log pi(response j
+ * | prompt) (device float [n_responses]), fp32 accumulation in a fixed order.
+ *
+ * psattn_logprob_bwd: dlogits (device [T, vocab], dt; fully overwritten) = gradient of
+ * sum_j d_resp_logp[j] * resp_logp[j]: every predicting row gets, per item, d_resp_logp[j] *
+ * (onehot(target) - softmax(row)); rows that predict nothing are written as zeros.
+ *
+ * psattn_dpo_loss: responses stored as (chosen, rejected) pairs: loss[i] = -log sigmoid(beta *
+ * ((pc - rc) - (pr - rr))) from policy and reference log-probabilities (device float
+ * [2 n_pairs] each); d_logp (device float [2 n_pairs], may be NULL) = d loss[i] / d policy
+ * log-probabilities.  (Eq. 1 is printed with a ratio of logarithms; it is read with the
+ * logarithm of the ratio, as DPO is defined.)
+ */
+int psattn_logprob_plan(int32_t n_samples, const int32_t* offset, const int32_t* prefix_len,
+                        const int32_t* resp_ptr, const int32_t* resp_len, int32_t total_tokens,
+                        void* hip_stream, psattn_lp_plan** out);
+int psattn_logprob_plan_free(psattn_lp_plan* plan);
+int psattn_logprob_plan_info(const psattn_lp_plan* plan, int32_t* n_responses, int32_t* n_rows, int64_t* n_items);
+int psattn_logprob_fwd(const psattn_lp_plan* plan, int32_t dt, int32_t vocab, const void* logits,
+                       const int32_t* token_ids, float* row_lse, float* resp_logp, void* hip_stream);
+int psattn_logprob_bwd(const psattn_lp_plan* plan, int32_t dt, int32_t vocab, const void* logits,
+                       const int32_t* token_ids, const float* row_lse, const float* d_resp_logp,
+                       void* dlogits, void* hip_stream);
+int psattn_dpo_loss(int32_t n_pairs, float beta, const float* logp_policy, const float* logp_ref,
+                    float* loss, float* d_logp, void* hip_stream);
 
 /*
  * Measurement aid (no part of the computation): issues the memory operations that a

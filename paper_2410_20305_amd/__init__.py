@@ -10,4 +10,5 @@ from .binding import (  # noqa: F401
     load_library, psattn_build_meta, psattn_bwd, psattn_bwd_workspace_bytes, psattn_fwd,
     psattn_kernel_name, psattn_profile_enable, psattn_profile_read, psattn_trim_pool, BF16, F32,
     psattn_bwd_static, psattn_bwd_static_max_rows, psattn_probe_dq_atomics, psattn_pack_ffd, psattn_build_meta_multi, Rope, psattn_fwd_rope, psattn_bwd_rope,
+    LogprobPlan, psattn_logprob_fwd, psattn_logprob_bwd, psattn_dpo_loss,
 )

@@ -23,6 +23,8 @@ EXPORTS = [
     "psattn_pack_ffd", "psattn_build_meta_multi", "psattn_build_meta_multi_host",
     "psattn_rope_create", "psattn_rope_free", "psattn_rope_k", "psattn_fwd_rope", "psattn_bwd_rope",
     "psattn_meta_copy_positions",
+    "psattn_logprob_plan", "psattn_logprob_plan_free", "psattn_logprob_plan_info", "psattn_logprob_fwd",
+    "psattn_logprob_bwd", "psattn_dpo_loss",
 ]
 
 
@@ -59,6 +61,12 @@ def load_library():
     lib.psattn_bwd_rope.argtypes = [vp, vp, i32, i32, i32, i32, f32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                     C.c_size_t, vp]
     lib.psattn_meta_copy_positions.argtypes = [vp, vp, pi32]
+    lib.psattn_logprob_plan.argtypes = [i32, vp, vp, vp, vp, i32, vp, C.POINTER(vp)]
+    lib.psattn_logprob_plan_free.argtypes = [vp]
+    lib.psattn_logprob_plan_info.argtypes = [vp, pi32, pi32, C.POINTER(i64)]
+    lib.psattn_logprob_fwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp]
+    lib.psattn_logprob_bwd.argtypes = [vp, i32, i32, vp, vp, vp, vp, vp, vp]
+    lib.psattn_dpo_loss.argtypes = [i32, f32, vp, vp, vp, vp, vp]
     lib.psattn_free_meta.argtypes = [vp]
     lib.psattn_free_meta_async.argtypes = [vp, vp]
     lib.psattn_trim_pool.argtypes = []
@@ -439,6 +447,88 @@ def psattn_bwd_rope(meta: Meta, rope: Rope, Qr, Kr, V, O, dO, LSE, scale, dQ=Non
                              workspace.numel() * workspace.element_size(), _stream_ptr(stream))
     _check(st, "psattn_bwd_rope")
     return dQ, dK, dV
+
+
+class LogprobPlan:
+    """Owner of a psattn_lp_plan handle."""
+
+    def __init__(self, offset, prefix_len, resp_ptr, resp_len, total_tokens, stream=None):
+        lib = load_library()
+        off, p, ptr, rl = _i32(offset), _i32(prefix_len), _i32(resp_ptr), _i32(resp_len)
+        h = C.c_void_p()
+        _check(lib.psattn_logprob_plan(off.shape[0], off.ctypes.data, p.ctypes.data, ptr.ctypes.data,
+                                       rl.ctypes.data if rl.shape[0] else None, int(total_tokens), _stream_ptr(stream),
+                                       C.byref(h)), "psattn_logprob_plan")
+        self._h = h
+        self.total_tokens = int(total_tokens)
+        a, b, c = C.c_int32(), C.c_int32(), C.c_int64()
+        _check(lib.psattn_logprob_plan_info(h, C.byref(a), C.byref(b), C.byref(c)), "psattn_logprob_plan_info")
+        self.n_responses, self.n_rows, self.n_items = a.value, b.value, c.value
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("plan already freed")
+        return self._h
+
+    def free(self):
+        if self._h is not None:
+            _check(load_library().psattn_logprob_plan_free(self._h), "psattn_logprob_plan_free")
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def psattn_logprob_fwd(plan: LogprobPlan, logits, token_ids, row_lse=None, resp_logp=None, stream=None):
+    """row_lse [T], resp_logp [n_responses] from logits [T, vocab] and token_ids int32 [T]."""
+    import torch
+    T, V = logits.shape
+    _check_tensor(logits, "logits", (plan.total_tokens, V), None)
+    _check_tensor(token_ids, "token_ids", (T,), torch.int32)
+    row_lse = torch.zeros(T, dtype=torch.float32, device=logits.device) if row_lse is None else row_lse
+    resp_logp = torch.empty(plan.n_responses, dtype=torch.float32, device=logits.device) if resp_logp is None else resp_logp
+    _check_tensor(row_lse, "row_lse", (T,), torch.float32)
+    _check_tensor(resp_logp, "resp_logp", (plan.n_responses,), torch.float32)
+    st = load_library().psattn_logprob_fwd(plan.handle, _dtype_code(logits), V, logits.data_ptr(), token_ids.data_ptr(),
+                                           row_lse.data_ptr(), resp_logp.data_ptr(), _stream_ptr(stream))
+    _check(st, "psattn_logprob_fwd")
+    return row_lse, resp_logp
+
+
+def psattn_logprob_bwd(plan: LogprobPlan, logits, token_ids, row_lse, d_resp_logp, dlogits=None, stream=None):
+    import torch
+    T, V = logits.shape
+    _check_tensor(logits, "logits", (plan.total_tokens, V), None)
+    _check_tensor(token_ids, "token_ids", (T,), torch.int32)
+    _check_tensor(row_lse, "row_lse", (T,), torch.float32)
+    _check_tensor(d_resp_logp, "d_resp_logp", (plan.n_responses,), torch.float32)
+    dlogits = torch.empty_like(logits) if dlogits is None else dlogits
+    _check_tensor(dlogits, "dlogits", logits.shape, logits.dtype)
+    st = load_library().psattn_logprob_bwd(plan.handle, _dtype_code(logits), V, logits.data_ptr(), token_ids.data_ptr(),
+                                           row_lse.data_ptr(), d_resp_logp.data_ptr(), dlogits.data_ptr(),
+                                           _stream_ptr(stream))
+    _check(st, "psattn_logprob_bwd")
+    return dlogits
+
+
+def psattn_dpo_loss(logp_policy, logp_ref, beta, stream=None):
+    """loss [n_pairs], d_logp [2 n_pairs] for responses stored as (chosen, rejected) pairs."""
+    import torch
+    n = logp_policy.shape[0]
+    if n % 2 or tuple(logp_ref.shape) != (n,):
+        raise ValueError("log-probabilities must come in (chosen, rejected) pairs")
+    _check_tensor(logp_policy, "logp_policy", (n,), torch.float32)
+    _check_tensor(logp_ref, "logp_ref", (n,), torch.float32)
+    loss = torch.empty(n // 2, dtype=torch.float32, device=logp_policy.device)
+    d = torch.empty(n, dtype=torch.float32, device=logp_policy.device)
+    st = load_library().psattn_dpo_loss(n // 2, float(beta), logp_policy.data_ptr(), logp_ref.data_ptr(), loss.data_ptr(),
+                                        d.data_ptr(), _stream_ptr(stream))
+    _check(st, "psattn_dpo_loss")
+    return loss, d
 
 
 def psattn_probe_dq_atomics(meta: Meta, n_q_heads, n_kv_heads, acc, mode, stream=None) -> None:

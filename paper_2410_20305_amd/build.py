@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsattn.so")
 SOURCES = ["psattn_meta.cpp", "psattn_pack.cpp", "psattn_api.hip", "psattn_generic.hip", "psattn_mfma_fwd.hip", "psattn_mfma_bwd.hip",
-           "psattn_mfma_dkdv.hip", "psattn_bwd_static.hip", "psattn_probe.hip", "psattn_rope.hip"]
+           "psattn_mfma_dkdv.hip", "psattn_bwd_static.hip", "psattn_probe.hip", "psattn_rope.hip", "psattn_logprob.hip"]
 
 # Packed-fp32 VALU instructions are switched off for all device code (the compiler
 # otherwise forms them from ordinary float arithmetic).

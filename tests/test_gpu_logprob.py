@@ -1,0 +1,78 @@
+"""Per-response log-probabilities, their backward and the DPO loss on the GPU (through the C ABI)
+against the oracle.  fp32 logits: log-probabilities within 1e-4 absolute of the fp64 oracle per
+response (sums of up to a few hundred fp32 terms), gradients within 1e-6; bf16 logits: the same
+forward bar (inputs are exact bf16 numbers, accumulation is fp32), gradient elements within half
+a bf16 ulp + 1e-6."""
+import numpy as np
+import pytest
+
+import paper_2410_20305_amd as ps
+import psattn_workloads as W
+from oracle import psattn_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+CASES = {
+    # off, P, ptr, rl, T, V
+    "two_responses_packed": ([3, 60], [20, 7], [0, 2, 4], [9, 14, 5, 11], 100, 1000),
+    "multi_and_empty": ([0, 30, 50], [5, 0, 4], [0, 3, 5, 5], [4, 0, 6, 3, 2], 60, 257),   # vocab not a multiple of 8
+    "single_token_responses": ([1], [2], [0, 2], [1, 1], 6, 64),
+}
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("case", sorted(CASES))
+def test_logprob_forward_backward(case, dtype):
+    import torch
+    off, P, ptr, rl, T, V = CASES[case]
+    rng = np.random.default_rng(301)
+    logits = (rng.standard_normal((T, V)) * 3).astype(np.float32)
+    if dtype == "bf16":
+        logits = W.bf16_round(logits)
+    ids = rng.integers(0, V, size=T).astype(np.int32)
+    ids[off[0] + P[0]:off[0] + P[0] + 1] = ids[off[0] + P[0] + rl[0]] if rl[0] and rl[1] else ids[off[0] + P[0]]  # two responses may start alike
+    d_logp = rng.standard_normal(len(rl)).astype(np.float32)
+    plan = ps.LogprobPlan(off, P, ptr, rl, T)
+    items = orc.prediction_items(off, P, ptr, rl)
+    assert plan.n_responses == len(rl) and plan.n_items == len(items)
+    assert plan.n_rows == len({r for _, r, _ in items})
+    dev = lambda x, dt=None: torch.from_numpy(x).to("cuda") if dt is None else torch.from_numpy(x).to("cuda").to(dt)
+    lg = dev(logits, torch.bfloat16 if dtype == "bf16" else torch.float32)
+    tid = dev(ids)
+    row_lse, logp = ps.psattn_logprob_fwd(plan, lg, tid)
+    dlog = torch.full_like(lg, float("nan"))
+    ps.psattn_logprob_bwd(plan, lg, tid, row_lse, dev(d_logp), dlogits=dlog)
+    torch.cuda.synchronize()
+    ref = orc.response_logprobs(logits, ids, off, P, ptr, rl)
+    assert np.abs(logp.cpu().numpy().astype(np.float64) - ref).max() <= 1e-4
+    gref = orc.response_logprobs_grad(logits, ids, off, P, ptr, rl, d_logp.astype(np.float64))
+    got = dlog.float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(got))
+    silent = np.abs(gref).sum(axis=1) == 0
+    assert np.all(got[silent] == 0)                                   # rows that predict nothing: exact zeros
+    tol = 1e-6 if dtype == "f32" else 2.0 ** -8 * np.abs(gref) + 1e-6   # half a bf16 ulp (8 significant bits)
+    excess = float((np.abs(got - gref) - tol).max())
+    assert excess <= 0, excess
+    plan.free()
+
+
+def test_dpo_loss_matches_oracle():
+    import torch
+    rng = np.random.default_rng(302)
+    lp = (rng.standard_normal(10) * 20 - 100).astype(np.float32)
+    lr = (lp + rng.standard_normal(10) * 5).astype(np.float32)
+    loss, d = ps.psattn_dpo_loss(torch.from_numpy(lp).cuda(), torch.from_numpy(lr).cuda(), 0.1)
+    ref_loss, ref_d = orc.dpo_loss(lp, lr, 0.1)
+    assert np.abs(loss.cpu().numpy() - ref_loss).max() <= 1e-5
+    assert np.abs(d.cpu().numpy() - ref_d).max() <= 1e-6
+    same, _ = ps.psattn_dpo_loss(torch.from_numpy(lp).cuda(), torch.from_numpy(lp).cuda(), 0.7)
+    assert np.abs(same.cpu().numpy() - np.log(2.0)).max() <= 1e-6   # policy == reference
+
+
+def test_logprob_errors():
+    with pytest.raises(ps.PsattnError) as e:
+        ps.LogprobPlan([0], [3], [0, 2], [2, 9], 8)                   # 14 tokens in a buffer of 8
+    assert e.value.status == -3
+    with pytest.raises(ps.PsattnError) as e:
+        ps.LogprobPlan([0, 2], [3, 1], [0, 1, 2], [2, 2], 20)         # overlap
+    assert e.value.status == -2
