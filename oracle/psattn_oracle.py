@@ -21,7 +21,10 @@ What it follows:
   * rotary position embedding with the position ids of Section 3.1 (every
     response restarts right behind the prompt, as in the paired format);
   * the total log-probability of every response and the DPO loss of Eq. 1
-    (Section 2.1), with their gradients.
+    (Section 2.1), with their gradients;
+  * a whole self-attention layer (projections, rotary embedding, attention,
+    output projection) with its explicit backward (Section 4.2's attention-layer
+    micro-benchmark).
 
 Readings where the paper is silent (all restated where they are used):
   - start indices are row-absolute positions (they are compared with q and kv);
@@ -46,7 +49,8 @@ optimum; for the rotary embedding explicit 2x2 rotation matrices, the
 relative-position property, finite differences, and equality with plain causal
 attention over [prompt | response] with ordinary positions; for the
 log-probabilities torch's cross entropy over the paired format, a closed form
-for uniform logits and autograd.  No function here is unpinned.
+for uniform logits and autograd; for the layer the same layer built from torch
+operations and differentiated by autograd.  No function here is unpinned.
 """
 from __future__ import annotations
 
@@ -609,3 +613,28 @@ def dpo_loss(logp_policy, logp_ref, beta):
     d[0::2] = beta * dz
     d[1::2] = -beta * dz
     return loss, d
+
+
+# --------------------------------------------------------------------------
+# a whole self-attention layer (the "attention layer" micro-benchmark of Section 4.2)
+# --------------------------------------------------------------------------
+def layer_backward(X, Wq, Wk, Wv, Wo, dY, scale, theta, D, B, mask, n_q_heads, n_kv_heads, round_act=None):
+    """y = attention(rope(x Wq^T), rope(x Wk^T), x Wv^T) Wo^T with its explicit backward.
+    X, dY [T, hidden]; weights [out_features, in_features].  `round_act(x)`, if given, is
+    applied wherever a bf16 model stores an activation (projections, rotated operands,
+    attention output, the gradients handed between the stages).  Returns Y, dX, dWq, dWk, dWv,
+    dWo (fp64)."""
+    r = (lambda x: x) if round_act is None else round_act
+    X, dY = np.asarray(X, dtype=np.float64), np.asarray(dY, dtype=np.float64)
+    Wq, Wk, Wv, Wo = (np.asarray(w, dtype=np.float64) for w in (Wq, Wk, Wv, Wo))
+    T = X.shape[0]
+    d = Wq.shape[0] // n_q_heads
+    Q = r(X @ Wq.T).reshape(T, n_q_heads, d)
+    K = r(X @ Wk.T).reshape(T, n_kv_heads, d)
+    V = r(X @ Wv.T).reshape(T, n_kv_heads, d)
+    dO = r(dY @ Wo).reshape(T, n_q_heads, d)
+    a = backward_rope(Q, K, V, dO, scale, theta, D, B, mask, round_operands=round_act)
+    O = r(a["O"]).reshape(T, -1)
+    dQ, dK, dV = (r(a[n]).reshape(T, -1) for n in ("dQ", "dK", "dV"))
+    return dict(Y=O @ Wo.T, dWo=dY.T @ O, dWq=dQ.T @ X, dWk=dK.T @ X, dWv=dV.T @ X,
+                dX=dQ @ Wq + dK @ Wk + dV @ Wv)
