@@ -28,6 +28,7 @@ import numpy as np  # noqa: E402
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 PEAK_HBM_GBS = 8000.0
+SWEEP_BATCH = 4             # samples per point of the length sweeps (enough work to fill the chip at the short end)
 LAYERS = 32                 # the block mask is built once per step and shared by every layer (Section 3.1)
 PASSES = ["fwd", "delta", "dq", "dkdv"]
 # algorithmic FLOPs per launch in units of d * Hq * N_allowed: forward 4 (S, PV); dQ pass 2 (dQ only: its
@@ -213,13 +214,13 @@ def cpu_baseline(w, tens, budget_s=20.0):
 
 
 def length_sweep(W, steps, warmup):
-    """Attention forward + backward time of one sample, prefix-shared against paired, over a
+    """Attention forward + backward time of a small batch, prefix-shared against paired, over a
     grid of prompt and completion lengths (Section 4.2's self-attention micro-benchmark:
     Mistral-7B-shaped heads, 32 q / 8 kv, d = 128; chosen and rejected of equal length)."""
     rows = []
     for p in (1024, 4096, 8192, 16384):
         for c in (128, 512, 2048, 4096):
-            w = W.custom_workload([(p, c, c)], hq=32, hkv=8, d=128, dtype="bf16", seed=p + c, name="sweep")
+            w = W.custom_workload([(p, c, c)] * SWEEP_BATCH, hq=32, hkv=8, d=128, dtype="bf16", seed=p + c, name="sweep")
             pw, _, _ = W.paired_workload(w)
             rs, rp = Runner(w, None, seed=1), Runner(pw, None, seed=1)
             ms_s, pp_s, _ = rs.timed(steps, warmup)
@@ -233,6 +234,54 @@ def length_sweep(W, steps, warmup):
     return rows
 
 
+def layer_sweep(W, steps, warmup):
+    """Forward + backward time of one whole self-attention layer on a small batch, prefix-shared against
+    paired (Section 4.2's attention-layer micro-benchmark: the projections are linear in the tokens,
+    the attention quadratic)."""
+    import torch
+    import paper_2410_20305_amd as ps
+    from paper_2410_20305_amd.layer import Layer
+    hidden, Hq, Hkv, d = 4096, 32, 8, 128
+    layer = Layer(hidden, Hq, Hkv, d)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    rnd = lambda *shape, s=1.0: (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * s).to(torch.bfloat16)
+    Wq, Wk, Wv = rnd(Hq * d, hidden, s=hidden ** -0.5), rnd(Hkv * d, hidden, s=hidden ** -0.5), rnd(Hkv * d, hidden, s=hidden ** -0.5)
+    Wo = rnd(hidden, Hq * d, s=(Hq * d) ** -0.5)
+    rope = ps.Rope(d, 10000.0, 32768)
+
+    def time_layout(w):
+        meta = ps.psattn_build_meta(w.offset, w.prefix_len, w.chosen_len, w.rejected_len, w.total_tokens)
+        T = w.total_tokens
+        X, dY = rnd(T, hidden), rnd(T, hidden)
+        ws = torch.empty(layer.workspace_bytes(meta), dtype=torch.uint8, device="cuda")
+        Y = torch.empty_like(X)
+        grads = tuple(torch.empty_like(t) for t in (X, Wq, Wk, Wv, Wo))
+        ts = []
+        for it in range(warmup + steps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            layer.forward(meta, rope, w.scale, X, Wq, Wk, Wv, Wo, ws, Y=Y)
+            layer.backward(meta, rope, w.scale, X, Wq, Wk, Wv, Wo, dY, ws, grads=grads)
+            b.record()
+            torch.cuda.synchronize()
+            if it >= warmup:
+                ts.append(a.elapsed_time(b))
+        meta.free()
+        return float(np.median(ts))
+
+    rows = []
+    for p in (1024, 4096, 8192, 16384):
+        for c in (128, 512, 2048):
+            w = W.custom_workload([(p, c, c)] * SWEEP_BATCH, hq=Hq, hkv=Hkv, d=d, dtype="bf16", seed=p + c, name="layer")
+            pw, _, _ = W.paired_workload(w)
+            ms_s, ms_p = time_layout(w), time_layout(pw)
+            rows.append(dict(prefix=p, completion=c, shared_ms=round(ms_s, 4), paired_ms=round(ms_p, 4),
+                             speedup=round(ms_p / ms_s, 3), token_ratio=round((2 * p + 2 * c) / (p + 2 * c), 3),
+                             attention_pair_ratio=round(allowed_pairs(pw) / allowed_pairs(w), 3)))
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,6 +291,8 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the other configurations and the paired baseline")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     ap.add_argument("--sweep", action="store_true", help="prefix x completion length grid instead of the configurations")
+    ap.add_argument("--layer", action="store_true",
+                    help="whole attention layer (projections + RoPE + attention + output projection), prefix x completion grid")
     ap.add_argument("--dq-atomics-probe", action="store_true",
                     help="time the fp32 atomic adds a one-pass backward would need for dQ, on every configuration")
     ap.add_argument("--copy-probe", action="store_true",
@@ -297,8 +348,13 @@ def main():
             del acc
         print(json.dumps({"metric": "dQ accumulation traffic of a one-pass backward, alone", "unit": "ms", "configs": res}))
         return
+    if args.layer:
+        print(json.dumps({"metric": "attention layer fwd+bwd ms, prefix-shared vs paired, batch of %d equal samples" % SWEEP_BATCH, "unit": "ms",
+                          "shape": "hidden 4096, 32q/8kv d128 bf16 (Mistral-7B attention layer), RoPE inside the op",
+                          "grid": layer_sweep(W, min(args.steps, 10), 2)}))
+        return
     if args.sweep:
-        print(json.dumps({"metric": "attention fwd+bwd ms, prefix-shared vs paired, one sample", "unit": "ms",
+        print(json.dumps({"metric": "attention fwd+bwd ms, prefix-shared vs paired, batch of %d equal samples" % SWEEP_BATCH, "unit": "ms",
                           "heads": "32q/8kv d128 bf16", "grid": length_sweep(W, min(args.steps, 10), 2)}))
         return
 

@@ -9,6 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsattn.so")
+LAYER_LIB = os.path.join(HERE, "libpsattn_layer.so")   # the attention-layer benchmark: libpsattn + rocBLAS
 SOURCES = ["psattn_meta.cpp", "psattn_pack.cpp", "psattn_api.hip", "psattn_generic.hip", "psattn_mfma_fwd.hip", "psattn_mfma_bwd.hip",
            "psattn_mfma_dkdv.hip", "psattn_bwd_static.hip", "psattn_probe.hip", "psattn_rope.hip", "psattn_logprob.hip"]
 
@@ -67,6 +68,13 @@ def build(verbose: bool = True, extra=()) -> str:
     if failed:
         raise RuntimeError("hipcc failed")
     cmd = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    # the layer library: host code only, links libpsattn.so (found next to it at run time) and rocBLAS
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-x", "hip",
+           "-I", os.path.join(ROOT, "include"), os.path.join(CSRC, "psattn_layer.cpp"), "-o", LAYER_LIB,
+           "-L", HERE, "-lpsattn", "-L/opt/rocm/lib", "-lrocblas", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath,/opt/rocm/lib"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

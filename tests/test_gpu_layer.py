@@ -1,0 +1,61 @@
+"""The attention layer (libpsattn_layer.so: rocBLAS projections + libpsattn attention with rotary
+embedding) against the oracle's layer.  The oracle rounds to bfloat16 wherever the GPU path stores
+an activation; what remains is the fp32-vs-fp64 accumulation and the bf16 rounding of the outputs.
+Bars: relative L2 <= 2e-2 per tensor (the bar the gradients of the attention itself have)."""
+import numpy as np
+import pytest
+
+import paper_2410_20305_amd as ps
+import psattn_workloads as W
+from oracle import psattn_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+def test_layer_exports():
+    from paper_2410_20305_amd.layer import load_layer_library
+    lib = load_layer_library()
+    for name in ("psattn_layer_create", "psattn_layer_free", "psattn_layer_workspace_bytes", "psattn_layer_fwd",
+                 "psattn_layer_bwd"):
+        assert hasattr(lib, name)
+
+
+@pytest.mark.parametrize("case", ["two_responses", "three_responses"])
+def test_layer_forward_backward(case):
+    import torch
+    from gpu_util import rel_l2, to_np
+    from paper_2410_20305_amd.layer import Layer
+    if case == "two_responses":
+        off, P, ptr, rl, T = [3, 300], [150, 64], [0, 2, 4], [40, 70, 90, 33], 500
+    else:
+        off, P, ptr, rl, T = [0], [130], [0, 3], [60, 33, 129], 360
+    hidden, Hq, Hkv, d, theta = 256, 4, 2, 128, 10000.0
+    scale = 1.0 / np.sqrt(d)
+    rng = np.random.default_rng(401)
+    bf = lambda x: W.bf16_round(x.astype(np.float32))
+    X, dY = bf(rng.standard_normal((T, hidden))), bf(rng.standard_normal((T, hidden)))
+    s = 1.0 / np.sqrt(hidden)
+    Wq, Wk, Wv = (bf(rng.standard_normal((h * d, hidden)) * s) for h in (Hq, Hkv, Hkv))
+    Wo = bf(rng.standard_normal((hidden, Hq * d)) / np.sqrt(Hq * d))
+    meta = ps.psattn_build_meta_multi(off, P, ptr, rl, T)
+    rope = ps.Rope(d, theta, meta.positions()[1])
+    layer = Layer(hidden, Hq, Hkv, d)
+    dev = lambda x: torch.from_numpy(x).to("cuda").to(torch.bfloat16)
+    tX, tWq, tWk, tWv, tWo, tdY = (dev(a) for a in (X, Wq, Wk, Wv, Wo, dY))
+    ws = torch.empty(layer.workspace_bytes(meta), dtype=torch.uint8, device="cuda")
+    Y = layer.forward(meta, rope, scale, tX, tWq, tWk, tWv, tWo, ws)
+    grads = layer.backward(meta, rope, scale, tX, tWq, tWk, tWv, tWo, tdY, ws)
+    torch.cuda.synchronize()
+    D, B = orc.branch_arrays(off, P, ptr, rl, T)
+    ref = orc.layer_backward(X, Wq, Wk, Wv, Wo, dY, scale, theta, D, B, lambda *a: orc.dense_branch_mask(D, B, *a), Hq, Hkv,
+                             round_act=lambda x: bf(x).astype(np.float64))
+    real = D >= 0
+    got = dict(Y=to_np(Y), dX=to_np(grads[0]), dWq=to_np(grads[1]), dWk=to_np(grads[2]), dWv=to_np(grads[3]), dWo=to_np(grads[4]))
+    assert np.all(got["Y"][~real] == 0)                       # padding rows: O = 0, so y = 0
+    for name in ("Y", "dX", "dWq", "dWk", "dWv", "dWo"):
+        assert np.all(np.isfinite(got[name])), name
+        e = rel_l2(got[name], ref[name])
+        assert e <= 2e-2, (name, e)
+    layer.free()
+    rope.free()
+    meta.free()

@@ -137,3 +137,16 @@ def test_library_exports_every_declared_symbol():
     lib = ctypes.CDLL(ps.lib_path())
     for name in sorted(declared):
         assert hasattr(lib, name), name
+
+
+def test_layer_library_exports_every_declared_symbol():
+    """include/psattn_layer.h against libpsattn_layer.so (loads rocBLAS; no device call is made)."""
+    from paper_2410_20305_amd.layer import load_layer_library
+    header = open(os.path.join(ROOT, "include", "psattn_layer.h")).read()
+    body = header[header.index("typedef struct psattn_layer"):]
+    declared = set(re.findall(r"\b(psattn_layer_[a-z_]+)\s*\(", body))
+    assert declared == {"psattn_layer_create", "psattn_layer_free", "psattn_layer_workspace_bytes", "psattn_layer_fwd",
+                        "psattn_layer_bwd"}
+    lib = load_layer_library()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
