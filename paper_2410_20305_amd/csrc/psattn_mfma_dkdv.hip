@@ -298,6 +298,11 @@ __global__ __launch_bounds__(256) void psattn_dkdv_bf16_mfma(AttnArgs a) {
         uint32_t mw[2][8];
         if (full) {
             dkdv_tile<true>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g, piece);
+        } else if (__builtin_amdgcn_ballot_w64(max(key, q0) < min(key_hi, q0 + 64)) == 0) {
+            // PARTIAL tile none of whose queries reads any of this wave's 32 keys (two of the four
+            // waves on the first q-tile of every causal diagonal, and the keys of another sample or
+            // response): the wave only issues its share of the next tile's copy
+            static_for<0, 9>([&](auto P) { piece(P); });
         } else {
             pair_masks(mw, key - q0, key_hi - q0, g);
             dkdv_tile<false>(sQ[buf], sG[buf], sL[buf], sD[buf], lo, mw, c, g, piece);
