@@ -102,11 +102,16 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
         // key of the tile only issues its share of the copy and leaves the SIMD to the other
         // workgroup's wave.
         uint32_t bits = 0xffffffffu;
+        // skip32[kb]: none of the wave's 32 queries reads any of the 32 keys of block kb (PARTIAL tiles
+        // only): the block's 24 MFMAs and its arithmetic are left out
+        bool skip32[2] = {false, false};
         if (!full) {
             bits = elem_range_bits(tk.s - k0, q_row + 1 - k0, g) & ~elem_range_bits(tk.hole_lo - k0, tk.hole_hi - k0, g);
-            if (__builtin_amdgcn_ballot_w64(bits != 0) == 0) {
+            skip32[0] = __builtin_amdgcn_ballot_w64((bits & 0xffffu) != 0) == 0;
+            skip32[1] = __builtin_amdgcn_ballot_w64((bits >> 16) != 0) == 0;
+            if (skip32[0]) {  // the next tile's copy rides on the first block's slots: issue it here instead
                 static_for<0, 8>([&](auto P) { pair_copy_piece<decltype(P)::value>(pc, sKb[buf ^ 1], sVb[buf ^ 1], w); });
-                return;
+                if (skip32[1]) return;
             }
         }
         const char* sK = sKb[buf];
@@ -125,9 +130,11 @@ __global__ __launch_bounds__(256, 2) void psattn_dq_bf16_mfma(AttnArgs a) {
                 }
             }
         };
-        static_for<0, kAhead>([&](auto M) { request(M); });
         static_for<0, 2>([&](auto KB) {
             constexpr int kb = decltype(KB)::value;
+            if (skip32[kb]) return;
+            // the first operands of a block are requested by the block before it, unless there is none
+            if (kb == 0 || skip32[0]) static_for<0, kAhead>([&](auto M) { request(std::integral_constant<int, 24 * kb + decltype(M)::value>{}); });
             f32x16 s, dp;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { s[i] = 0.f; dp[i] = 0.f; }

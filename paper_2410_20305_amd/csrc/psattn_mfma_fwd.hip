@@ -141,6 +141,13 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
                 s[e >> 4][e & 15] = keep_or_neg_inf<e>(s[e >> 4][e & 15], bits);
             });
         }
+        // The maxima below are taken by inline assembly (max3), which the compiler does not treat as a
+        // vector-ALU reader of MFMA results when it places wait states, so the wait states between the
+        // last S MFMA and them are put here by hand (an MFMA of this shape needs up to 18 before the
+        // vector ALU may read its result; without them the maxima were seen to read scores of the
+        // previous tile now and then).  The statement names the scores as operands so that the maxima
+        // cannot be moved above it.
+        asm volatile("s_nop 15\n\ts_nop 3" : "+v"(s[0]), "+v"(s[1]));
         // four independent chains each for the maximum and (below) the sum
         float mxp[4];
 #pragma unroll
