@@ -293,6 +293,7 @@ def main():
     ap.add_argument("--sweep", action="store_true", help="prefix x completion length grid instead of the configurations")
     ap.add_argument("--layer", action="store_true",
                     help="whole attention layer (projections + RoPE + attention + output projection), prefix x completion grid")
+    ap.add_argument("--mfma-probe", action="store_true", help="time an MFMA-only kernel: the matrix-core ceiling under load")
     ap.add_argument("--dq-atomics-probe", action="store_true",
                     help="time the fp32 atomic adds a one-pass backward would need for dQ, on every configuration")
     ap.add_argument("--copy-probe", action="store_true",
@@ -321,6 +322,31 @@ def main():
         torch.cuda.synchronize()
         print(json.dumps({"copy_probe_bytes_read": src.numel() * 4, "copy_probe_bytes_written": src.numel() * 4,
                           "launches": 5}))
+        return
+    if args.mfma_probe:
+        # matrix-core ceiling of this device under load: MFMA-only kernel, 1 and 2 waves per SIMD
+        lib = ps.load_library()
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+        res = {}
+        for label, n_wg in (("one_wave_per_simd", 256), ("two_waves_per_simd", 512)):
+            iters = 20000
+            ts = []
+            for _ in range(5):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                st = lib.psattn_probe_mfma_peak(n_wg, iters, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+                b.record()
+                torch.cuda.synchronize()
+                assert st == 0
+                ts.append(a.elapsed_time(b))
+            ms = float(np.median(ts[1:]))
+            flops = n_wg * 4 * 4 * iters * 32768
+            res[label] = dict(workgroups=n_wg, mfma_per_wave=4 * iters, ms=round(ms, 4),
+                              tflops=round(flops / (ms * 1e-3) / 1e12, 1),
+                              frac_of_published_peak=round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                              cycles_per_mfma_at_2p4GHz=round(ms * 1e-3 * 2.4e9 / (4 * iters * (n_wg // 256)), 2))
+        print(json.dumps({"metric": "bf16 MFMA-only kernel (v_mfma_f32_32x32x16_bf16, register operands)", "unit": "TFLOP/s",
+                          "published_peak": PEAK_BF16_TFLOPS, "runs": res}))
         return
     if args.dq_atomics_probe:
         # the memory operations a one-pass backward would add for dQ, timed alone (see include/psattn.h)

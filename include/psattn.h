@@ -373,6 +373,14 @@ int psattn_dpo_loss(int32_t n_pairs, float beta, const float* logp_policy, const
 int psattn_probe_dq_atomics(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads, float* acc,
                             int32_t mode, void* hip_stream);
 
+/*
+ * Measurement aid: the matrix-core ceiling.  Launches n_workgroups workgroups of 4 waves that each
+ * issue 4 * iters back-to-back v_mfma_f32_32x32x16_bf16 (32 768 FLOPs each per wave) on register
+ * operands, with no memory traffic; sink is one device float that is never written.  FLOPs
+ * launched = n_workgroups * 4 * 4 * iters * 32768.
+ */
+int psattn_probe_mfma_peak(int32_t n_workgroups, int32_t iters, float* sink, void* hip_stream);
+
 /* Name of the kernel that psattn_fwd / psattn_bwd launched most recently in this
  * process for the given pass (0 = forward, 1 = delta, 2 = dQ, 3 = dK/dV), for profilers
  * and benchmarks; before any launch of that pass, the kernel a default-grid call with

@@ -19,7 +19,7 @@ EXPORTS = [
     "psattn_meta_allowed_pairs", "psattn_fwd", "psattn_bwd", "psattn_bwd_workspace_bytes",
     "psattn_kernel_name", "psattn_strerror", "psattn_profile_enable", "psattn_profile_read",
     "psattn_free_meta_async", "psattn_trim_pool", "psattn_uses_mfma",
-    "psattn_bwd_static", "psattn_bwd_static_max_rows", "psattn_probe_dq_atomics",
+    "psattn_bwd_static", "psattn_bwd_static_max_rows", "psattn_probe_dq_atomics", "psattn_probe_mfma_peak",
     "psattn_pack_ffd", "psattn_build_meta_multi", "psattn_build_meta_multi_host",
     "psattn_rope_create", "psattn_rope_free", "psattn_rope_k", "psattn_fwd_rope", "psattn_bwd_rope",
     "psattn_meta_copy_positions",
@@ -35,7 +35,8 @@ class PsattnError(RuntimeError):
 
 
 def lib_path() -> str:
-    return os.path.join(_HERE, "libpsattn.so")
+    # PSATTN_LIB: another build of the same library, for A/B measurements of kernel variants
+    return os.environ.get("PSATTN_LIB") or os.path.join(_HERE, "libpsattn.so")
 
 
 def load_library():
@@ -83,6 +84,7 @@ def load_library():
     lib.psattn_bwd_static_max_rows.argtypes = []
     lib.psattn_bwd_static_max_rows.restype = C.c_size_t
     lib.psattn_probe_dq_atomics.argtypes = [vp, i32, i32, vp, i32, vp]
+    lib.psattn_probe_mfma_peak.argtypes = [i32, i32, vp, vp]
     lib.psattn_pack_ffd.argtypes = [i32, vp, vp, vp, i32, i32, vp, vp, pi32, C.POINTER(i64)]
     lib.psattn_bwd_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.psattn_bwd_workspace_bytes.restype = C.c_size_t

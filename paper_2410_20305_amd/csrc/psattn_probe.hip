@@ -38,8 +38,35 @@ __global__ __launch_bounds__(256) void psattn_dq_atomics_probe(DeviceMeta meta, 
     }
 }
 
+// What the matrix cores sustain when nothing else issues: every wave runs `iters` rounds of four
+// independent v_mfma_f32_32x32x16_bf16 chains on register operands (no memory traffic at all).
+// With the clock the device holds under this load it is the ceiling any MFMA-bound kernel has.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 probe_bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float probe_f32x16;
+
+__global__ __launch_bounds__(256) void psattn_mfma_peak_probe(int iters, float* sink) {
+    probe_bf16x8 a, b;
+    for (int j = 0; j < 8; ++j) { a[j] = static_cast<__bf16>(1.0f + threadIdx.x * 1e-3f); b[j] = static_cast<__bf16>(0.5f); }
+    probe_f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+    for (int i = 0; i < iters; ++i) {
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    }
+    float r = 0.f;
+    for (int j = 0; j < 16; ++j) r += c0[j] + c1[j] + c2[j] + c3[j];
+    if (r == 12345.678f) sink[0] = r;  // keeps the chains alive; never true
+}
+
 }  // namespace
 }  // namespace psattn
+
+extern "C" int psattn_probe_mfma_peak(int32_t n_workgroups, int32_t iters, float* sink, void* hip_stream) {
+    if (n_workgroups <= 0 || iters <= 0 || !sink) return PSATTN_EINVAL;
+    psattn::psattn_mfma_peak_probe<<<n_workgroups, 256, 0, static_cast<hipStream_t>(hip_stream)>>>(iters, sink);
+    return hipGetLastError() == hipSuccess ? PSATTN_OK : PSATTN_EHIP;
+}
 
 extern "C" int psattn_probe_dq_atomics(const psattn_meta* meta, int32_t n_q_heads, int32_t n_kv_heads, float* acc,
                                        int32_t mode, void* hip_stream) {
