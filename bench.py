@@ -142,20 +142,38 @@ class Runner:
         return (t1 - t0) / steps * 1e3, per_pass, per_step
 
 
+def kernel_algorithmic_bytes(w, i):
+    """Bytes pass i (0 forward, 2 dQ, 3 dK/dV) must move per launch, each tensor once (bf16 tensors,
+    fp32 statistics); per token, times the buffer's tokens."""
+    Hq, Hkv, d, e = w.n_q_heads, w.n_kv_heads, w.head_dim, 2
+    per_token = {0: (Hq + 2 * Hkv) * d * e + Hq * d * e + 4 * Hq,
+                 2: (3 * Hq + 2 * Hkv) * d * e + 4 * Hq + Hq * d * e + 8 * Hq,
+                 3: (2 * Hq + 2 * Hkv) * d * e + 8 * Hq + 2 * Hkv * d * e}[i]
+    return w.total_tokens * per_token
+
+
 def roofline_of(w, per_pass, ps, traffic_table, name):
-    """Roofline object of the dominant kernel of one workload."""
+    """Roofline object of the dominant kernel of one workload, against whichever of the two limits
+    (bf16 MFMA peak for its algorithmic FLOPs, HBM bandwidth for its algorithmic bytes) binds it."""
     dom = max((0, 2, 3), key=lambda i: per_pass[i])
     n_allowed = allowed_pairs(w)
     flops = ALG_UNITS[dom] * w.head_dim * w.n_q_heads * n_allowed
-    ach = flops / (per_pass[dom] * 1e-3) / 1e12
+    nbytes = kernel_algorithmic_bytes(w, dom)
+    t = per_pass[dom] * 1e-3
     kernel = ps.psattn_kernel_name(1, dom)
-    t = traffic_table.get("%s/%s" % (name, kernel))
-    return dict(bound="mfma", kernel=kernel, achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                frac=round(ach / PEAK_BF16_TFLOPS, 4),
-                traffic=int(t["read_bytes"] + t["write_bytes"]) if t else None,
-                traffic_source="rocprofv3 FETCH_SIZE/WRITE_SIZE summary committed under profiles/hbm_traffic.txt "
-                               "(not measured by this run)" if t else None,
-                avg_launch_ms=round(per_pass[dom], 4), algorithmic_flops_per_launch=flops)
+    tr = traffic_table.get("%s/%s" % (name, kernel))
+    common = dict(kernel=kernel, traffic=int(tr["read_bytes"] + tr["write_bytes"]) if tr else None,
+                  traffic_source="rocprofv3 FETCH_SIZE/WRITE_SIZE summary committed under profiles/hbm_traffic.txt "
+                                 "(not measured by this run)" if tr else None,
+                  avg_launch_ms=round(per_pass[dom], 4), algorithmic_flops_per_launch=flops,
+                  algorithmic_bytes_per_launch=nbytes)
+    if nbytes / (PEAK_HBM_GBS * 1e9) > flops / (PEAK_BF16_TFLOPS * 1e12):
+        ach = nbytes / t / 1e9
+        return dict(bound="hbm", achieved=round(ach, 1), peak=PEAK_HBM_GBS, unit="GB/s", frac=round(ach / PEAK_HBM_GBS, 4),
+                    **common)
+    ach = flops / t / 1e12
+    return dict(bound="mfma", achieved=round(ach, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                frac=round(ach / PEAK_BF16_TFLOPS, 4), **common)
 
 
 def summarize(w, ms_step, per_pass, per_step, flops):
