@@ -69,6 +69,22 @@ def test_dpo_loss_matches_oracle():
     assert np.abs(same.cpu().numpy() - np.log(2.0)).max() <= 1e-6   # policy == reference
 
 
+def test_logprob_no_responses_and_no_samples():
+    """Samples without responses predict nothing: every gradient row is zero; an empty table is accepted."""
+    import torch
+    plan = ps.LogprobPlan([0, 6], [4, 3], [0, 0, 0], [], 10)
+    assert plan.n_responses == 0 and plan.n_rows == 0 and plan.n_items == 0
+    lg = torch.randn((10, 32), device="cuda")
+    tid = torch.zeros(10, dtype=torch.int32, device="cuda")
+    row_lse, logp = ps.psattn_logprob_fwd(plan, lg, tid)
+    g = torch.full_like(lg, float("nan"))
+    ps.psattn_logprob_bwd(plan, lg, tid, row_lse, logp, dlogits=g)
+    torch.cuda.synchronize()
+    assert logp.numel() == 0 and float(g.abs().max()) == 0
+    empty = ps.LogprobPlan([], [], [0], [], 4)
+    assert empty.n_responses == 0
+
+
 def test_logprob_errors():
     with pytest.raises(ps.PsattnError) as e:
         ps.LogprobPlan([0], [3], [0, 2], [2, 9], 8)                   # 14 tokens in a buffer of 8

@@ -92,6 +92,28 @@ def test_rope_multi_response_and_large_theta():
 
 
 @pytest.mark.gpu
+def test_rope_degenerate_buffers():
+    """Nothing but padding, and a one-token sample: outputs are zeros / the token's own V row."""
+    import torch
+    rope = ps.Rope(128, 10000.0, 8)
+    meta = ps.psattn_build_meta([], [], [], [], 70)
+    q = torch.randn((70, 2, 128), device="cuda").to(torch.bfloat16)
+    k = torch.randn((70, 1, 128), device="cuda").to(torch.bfloat16)
+    O, LSE, Qr, Kr = ps.psattn_fwd_rope(meta, rope, q, k, k, 0.1)
+    dQ, dK, dV = ps.psattn_bwd_rope(meta, rope, Qr, Kr, k, O, q, LSE, 0.1)
+    torch.cuda.synchronize()
+    assert float(O.float().abs().max()) == 0 and torch.isneginf(LSE).all()
+    assert all(float(x.float().abs().max()) == 0 for x in (dQ, dK, dV))
+    meta = ps.psattn_build_meta([3], [1], [0], [0], 5)
+    q, k, v = q[:5].contiguous(), k[:5].contiguous(), torch.randn((5, 1, 128), device="cuda").to(torch.bfloat16)
+    O, LSE, Qr, Kr = ps.psattn_fwd_rope(meta, rope, q, k, v, 0.1)
+    torch.cuda.synchronize()
+    assert torch.equal(O[3, 0], v[3, 0]) and torch.equal(O[3, 1], v[3, 0])     # one key: O is its V row
+    assert torch.equal(Qr[3], q[3]) and torch.equal(Kr[3], k[3])               # position 0: unrotated
+    assert float(O[[0, 1, 2, 4]].float().abs().max()) == 0
+
+
+@pytest.mark.gpu
 def test_rope_errors():
     import torch
     w = W.custom_workload([(100, 40, 30)], hq=2, hkv=1, d=128, dtype="bf16", seed=203)
