@@ -339,6 +339,9 @@ int psattn_meta_copy_positions(const psattn_meta* meta, int32_t* pos /* host [T]
  * something (device float [T]; other entries untouched) and resp_logp[j] = log pi(response j
  * | prompt) (device float [n_responses]), fp32 accumulation in a fixed order.
  *
+ * A token id outside [0, vocab) contributes nothing to its response (and nothing is read or
+ * written for it).
+ *
  * psattn_logprob_bwd: dlogits (device [T, vocab], dt; fully overwritten) = gradient of
  * sum_j d_resp_logp[j] * resp_logp[j]: every predicting row gets, per item, d_resp_logp[j] *
  * (onehot(target) - softmax(row)); rows that predict nothing are written as zeros.

@@ -155,6 +155,7 @@ __global__ __launch_bounds__(kThreads) void psattn_lp_resp_sum(const int32_t* re
         const int row = u == 0 ? prev : first + u - 1;
         if (row < 0) continue;  // empty prompt: nothing predicts the first token
         const int tok = token_ids[first + u];
+        if (tok < 0 || tok >= vocab) continue;  // not a token of this vocabulary: contributes nothing
         acc += ld1(logits + static_cast<size_t>(row) * vocab + tok) - row_lse[row];
     }
     acc = block_sum(acc, sm);
@@ -184,9 +185,16 @@ __global__ __launch_bounds__(kThreads) void psattn_lp_bwd(const int32_t* row_des
     int r0, r1;
     if (desc >= 0) { r0 = desc; r1 = desc + 1; }
     else { const int i = -2 - desc; r0 = samp_ptr[i]; r1 = samp_ptr[i + 1]; }
+    // target token of item j of this row, -1 if the item does not exist (empty response) or its token
+    // is not of this vocabulary
+    auto target = [&](int j) {
+        if (desc < 0 && resp_len[j] == 0) return -1;
+        const int t = desc >= 0 ? token_ids[row + 1] : token_ids[resp_first[j]];
+        return t >= 0 && t < vocab ? t : -1;
+    };
     float coef = 0.f;
     for (int j = r0; j < r1; ++j)
-        if (desc >= 0 || resp_len[j] > 0) coef += d_logp[j];
+        if (target(j) >= 0) coef += d_logp[j];
     const float lse = row_lse[row];
     for (int c = threadIdx.x; c < n_vec; c += kThreads) {
         float v[N];
@@ -202,14 +210,11 @@ __global__ __launch_bounds__(kThreads) void psattn_lp_bwd(const int32_t* row_des
     __syncthreads();
     if (threadIdx.x == 0) {
         for (int j = r0; j < r1; ++j) {
-            if (desc < 0 && resp_len[j] == 0) continue;
-            const int tgt = desc >= 0 ? token_ids[row + 1] : token_ids[resp_first[j]];
+            const int tgt = target(j);
+            if (tgt < 0) continue;
             float v = -coef * __expf(ld1(x + tgt) - lse);
-            for (int k = r0; k < r1; ++k) {
-                if (desc < 0 && resp_len[k] == 0) continue;
-                const int tk = desc >= 0 ? tgt : token_ids[resp_first[k]];
-                if (tk == tgt) v += d_logp[k];
-            }
+            for (int k = r0; k < r1; ++k)
+                if (target(k) == tgt) v += d_logp[k];
             st1(g + tgt, v);
         }
     }
