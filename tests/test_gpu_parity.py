@@ -339,6 +339,37 @@ def test_bf16_nonpositive_scale_uses_generic_kernels():
     compare_full(w, tens, out, "bf16")
 
 
+def test_meta_pool_reuse_and_trim():
+    """Block masks come from pooled buffers: many builds and stream-ordered releases of different
+    sizes in a row, results of a forward through a recycled buffer stay exact, trimming is safe."""
+    import torch
+    w = W.custom_workload([(150, 40, 70), (30, 90, 10)], offsets=[5, 300], total_tokens=450, hq=2, hkv=1, d=128,
+                          dtype="bf16", seed=95)
+    tens = W.make_tensors(w)
+    ref, _ = run_gpu(w, tens)
+    from gpu_util import to_dev, to_np
+    Q, K, V = (to_dev(tens[n], "bf16") for n in ("Q", "K", "V"))
+    held = []
+    for i in range(24):
+        big = W.custom_workload([(64 * (1 + i % 5), 30, 20)], hq=2, hkv=1, d=128, dtype="bf16", seed=96)
+        mb = ps.psattn_build_meta(big.offset, big.prefix_len, big.chosen_len, big.rejected_len, big.total_tokens)
+        m = ps.psattn_build_meta(w.offset, w.prefix_len, w.chosen_len, w.rejected_len, w.total_tokens)
+        O, LSE = ps.psattn_fwd(m, Q, K, V, w.scale)
+        m.free_async()
+        if i % 3 == 0:
+            held.append(mb)          # stays alive across the trim below
+        else:
+            mb.free_async()
+        if i == 12:
+            ps.psattn_trim_pool()
+        torch.cuda.synchronize()
+        assert np.array_equal(to_np(O), ref["O"])
+    for mb in held:
+        assert mb.allowed_pairs() > 0
+        mb.free()
+    ps.psattn_trim_pool()
+
+
 def test_api_errors_on_device():
     import torch
     w = W.custom_workload([(10, 4, 6)], hq=2, hkv=1, d=128, dtype="bf16", seed=91)
