@@ -342,29 +342,43 @@ def main():
                           "launches": 5}))
         return
     if args.mfma_probe:
-        # matrix-core ceiling of this device under load: MFMA-only kernel, 1 and 2 waves per SIMD
+        # matrix-core ceiling of this device under load: MFMA-only kernel, 1, 2 and 4 waves per SIMD, on one constant
+        # operand pair, on random operands and on constant values spread over eight register sets; then the attention kernels themselves on all-zero inputs (same instruction
+        # stream, idle data paths), which separates what the clock costs from what the schedule costs
         lib = ps.load_library()
         sink = torch.zeros(1, dtype=torch.float32, device="cuda")
         res = {}
-        for label, n_wg in (("one_wave_per_simd", 256), ("two_waves_per_simd", 512)):
-            iters = 20000
-            ts = []
-            for _ in range(5):
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                st = lib.psattn_probe_mfma_peak(n_wg, iters, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
-                b.record()
-                torch.cuda.synchronize()
-                assert st == 0
-                ts.append(a.elapsed_time(b))
-            ms = float(np.median(ts[1:]))
-            flops = n_wg * 4 * 4 * iters * 32768
-            res[label] = dict(workgroups=n_wg, mfma_per_wave=4 * iters, ms=round(ms, 4),
-                              tflops=round(flops / (ms * 1e-3) / 1e12, 1),
-                              frac_of_published_peak=round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-                              cycles_per_mfma_at_2p4GHz=round(ms * 1e-3 * 2.4e9 / (4 * iters * (n_wg // 256)), 2))
+        for mode, operands in enumerate(("constant", "random", "constant_in_eight_registers")):
+            for label, n_wg in (("one_wave_per_simd", 256), ("two_waves_per_simd", 512), ("four_waves_per_simd", 1024)):
+                iters = 20000
+                ts = []
+                for _ in range(5):
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    st = lib.psattn_probe_mfma_peak(n_wg, iters, mode, sink.data_ptr(),
+                                                    torch.cuda.current_stream().cuda_stream)
+                    b.record()
+                    torch.cuda.synchronize()
+                    assert st == 0
+                    ts.append(a.elapsed_time(b))
+                ms = float(np.median(ts[1:]))
+                flops = n_wg * 4 * 4 * iters * 32768
+                res[operands + "_operands_" + label] = dict(
+                    workgroups=n_wg, mfma_per_wave=4 * iters, ms=round(ms, 4), tflops=round(flops / (ms * 1e-3) / 1e12, 1),
+                    frac_of_published_peak=round(flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                    cycles_per_mfma_at_2p4GHz=round(ms * 1e-3 * 2.4e9 / (4 * iters * (n_wg // 256)), 2))
+        w = W.make_workload(args.workload)
+        r = Runner(w, None, seed=w.seed)
+        kernels = {}
+        for label in ("workload_inputs", "zero_inputs"):
+            if label == "zero_inputs":
+                for x in (r.Q, r.K, r.V, r.dO):
+                    x.zero_()
+            _, pp, _ = r.timed(10, 3)
+            kernels[label] = dict(ms_fwd=round(pp[0], 4), ms_dq=round(pp[2], 4), ms_dkdv=round(pp[3], 4))
         print(json.dumps({"metric": "bf16 MFMA-only kernel (v_mfma_f32_32x32x16_bf16, register operands)", "unit": "TFLOP/s",
-                          "published_peak": PEAK_BF16_TFLOPS, "runs": res}))
+                          "published_peak": PEAK_BF16_TFLOPS, "runs": res,
+                          "attention_kernels": dict(workload=w.name, **kernels)}))
         return
     if args.dq_atomics_probe:
         # the memory operations a one-pass backward would add for dQ, timed alone (see include/psattn.h)

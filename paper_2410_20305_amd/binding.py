@@ -84,7 +84,7 @@ def load_library():
     lib.psattn_bwd_static_max_rows.argtypes = []
     lib.psattn_bwd_static_max_rows.restype = C.c_size_t
     lib.psattn_probe_dq_atomics.argtypes = [vp, i32, i32, vp, i32, vp]
-    lib.psattn_probe_mfma_peak.argtypes = [i32, i32, vp, vp]
+    lib.psattn_probe_mfma_peak.argtypes = [i32, i32, i32, vp, vp]
     lib.psattn_pack_ffd.argtypes = [i32, vp, vp, vp, i32, i32, vp, vp, pi32, C.POINTER(i64)]
     lib.psattn_bwd_workspace_bytes.argtypes = [vp, i32, i32, i32]
     lib.psattn_bwd_workspace_bytes.restype = C.c_size_t

@@ -41,18 +41,48 @@ __global__ __launch_bounds__(256) void psattn_dq_atomics_probe(DeviceMeta meta, 
 // What the matrix cores sustain when nothing else issues: every wave runs `iters` rounds of four
 // independent v_mfma_f32_32x32x16_bf16 chains on register operands (no memory traffic at all).
 // With the clock the device holds under this load it is the ceiling any MFMA-bound kernel has.
+// MODE 0: one constant fragment per operand side (the data paths hardly toggle).
+// MODE 1: eight different fragments per side with values spread like the workloads' (zero-mean,
+// unit scale), a different pair on every MFMA: the clock the device then holds depends on the data.
+// MODE 2: the register pattern of mode 1 with the constant values of mode 0 (tells the data apart
+// from the operand registers changing on every MFMA).
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 probe_bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float probe_f32x16;
 
+__device__ inline float probe_value(uint32_t key) {  // sum of four uniforms: zero mean, unit variance, bell-shaped
+    float v = 0.f;
+    for (int r = 0; r < 4; ++r) {
+        key = key * 1664525u + 1013904223u;
+        key ^= key >> 15;
+        key *= 2246822519u;
+        key ^= key >> 13;
+        v += static_cast<float>(key >> 8) * (1.0f / 16777216.0f) - 0.5f;
+    }
+    return v * 1.7320508f;
+}
+
+template <int MODE>
 __global__ __launch_bounds__(256) void psattn_mfma_peak_probe(int iters, float* sink) {
-    probe_bf16x8 a, b;
-    for (int j = 0; j < 8; ++j) { a[j] = static_cast<__bf16>(1.0f + threadIdx.x * 1e-3f); b[j] = static_cast<__bf16>(0.5f); }
+    constexpr int F = MODE ? 8 : 1;
+    constexpr bool RANDOM = MODE == 1;
+    probe_bf16x8 a[F], b[F];
+    for (int f = 0; f < F; ++f)
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t key = ((blockIdx.x * 256u + threadIdx.x) * 8u + f) * 16u + j;
+            a[f][j] = static_cast<__bf16>(RANDOM ? probe_value(2u * key) : 1.0f + threadIdx.x * 1e-3f);
+            b[f][j] = static_cast<__bf16>(RANDOM ? probe_value(2u * key + 1u) : 0.5f);
+        }
+    for (int f = 0; f < F; ++f) asm volatile("" : "+v"(a[f]), "+v"(b[f]));  // every fragment in registers of its own
     probe_f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
-    for (int i = 0; i < iters; ++i) {
-        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c0, 0, 0, 0);
-        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c1, 0, 0, 0);
-        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c2, 0, 0, 0);
-        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c3, 0, 0, 0);
+    for (int i = 0; i < iters; i += 2) {  // eight MFMAs per turn; `iters` is even
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[1 % F], b[1 % F], c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[2 % F], b[2 % F], c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[3 % F], b[3 % F], c3, 0, 0, 0);
+        c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[4 % F], b[4 % F], c0, 0, 0, 0);
+        c1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[5 % F], b[5 % F], c1, 0, 0, 0);
+        c2 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[6 % F], b[6 % F], c2, 0, 0, 0);
+        c3 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[7 % F], b[7 % F], c3, 0, 0, 0);
     }
     float r = 0.f;
     for (int j = 0; j < 16; ++j) r += c0[j] + c1[j] + c2[j] + c3[j];
@@ -62,9 +92,13 @@ __global__ __launch_bounds__(256) void psattn_mfma_peak_probe(int iters, float* 
 }  // namespace
 }  // namespace psattn
 
-extern "C" int psattn_probe_mfma_peak(int32_t n_workgroups, int32_t iters, float* sink, void* hip_stream) {
-    if (n_workgroups <= 0 || iters <= 0 || !sink) return PSATTN_EINVAL;
-    psattn::psattn_mfma_peak_probe<<<n_workgroups, 256, 0, static_cast<hipStream_t>(hip_stream)>>>(iters, sink);
+extern "C" int psattn_probe_mfma_peak(int32_t n_workgroups, int32_t iters, int32_t random_operands, float* sink,
+                                      void* hip_stream) {
+    if (n_workgroups <= 0 || iters <= 0 || (iters & 1) || random_operands < 0 || random_operands > 2 || !sink) return PSATTN_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (random_operands == 1) psattn::psattn_mfma_peak_probe<1><<<n_workgroups, 256, 0, st>>>(iters, sink);
+    else if (random_operands == 2) psattn::psattn_mfma_peak_probe<2><<<n_workgroups, 256, 0, st>>>(iters, sink);
+    else psattn::psattn_mfma_peak_probe<0><<<n_workgroups, 256, 0, st>>>(iters, sink);
     return hipGetLastError() == hipSuccess ? PSATTN_OK : PSATTN_EHIP;
 }
 
