@@ -176,6 +176,28 @@ def roofline_of(w, per_pass, ps, traffic_table, name):
                 frac=round(ach / PEAK_BF16_TFLOPS, 4), **common)
 
 
+def mfma_ceiling(ps, torch, reps=4):
+    """What an MFMA-only kernel sustains right now on this device on operands whose sign and mantissa bits are
+    random (the clock the device holds under matrix load depends on how much the data toggles): TFLOP/s, from the
+    difference of two launch lengths so that launch overhead cancels."""
+    lib = ps.load_library()
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda")
+    n_wg, t = 512, {}
+    for iters in (4000, 12000):
+        ts = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            st = lib.psattn_probe_mfma_peak(n_wg, iters, 1, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+            b.record()
+            torch.cuda.synchronize()
+            if st != 0:
+                return None
+            ts.append(a.elapsed_time(b))
+        t[iters] = float(np.median(ts[1:]))
+    return n_wg * 16 * 8000 * 32768 / ((t[12000] - t[4000]) * 1e-3) / 1e12
+
+
 def summarize(w, ms_step, per_pass, per_step, flops):
     kern = sum(per_pass)
     t_mfma = flops / (PEAK_BF16_TFLOPS * 1e12) * 1e3
@@ -450,6 +472,21 @@ def main():
         "detail": main_res,
         "roofline": roofline_of(w, per_pass, ps, traffic_table, args.workload),
     }
+    # the device's own matrix-core ceiling, measured in this run (MFMA-only kernel on operands with random sign and
+    # mantissa bits), beside the published peak the roofline object is priced against
+    ceil = mfma_ceiling(ps, torch)
+    if ceil:
+        executed = {0: 4, 2: 6, 3: 8}   # contraction units a pass executes (the dQ pass recomputes S and dP)
+        units = w.head_dim * w.n_q_heads * n_allowed
+        t_bound = sum(executed.values()) * units / (ceil * 1e12) * 1e3
+        out["mfma_ceiling"] = {
+            "what": "MFMA-only kernel (v_mfma_f32_32x32x16_bf16, register operands with random sign and mantissa bits), "
+                    "measured in this run",
+            "tflops": round(ceil, 1), "frac_of_published_peak": round(ceil / PEAK_BF16_TFLOPS, 4),
+            "dominant_kernel_achieved_over_ceiling": round(out["roofline"]["achieved"] / ceil, 4)
+            if out["roofline"]["bound"] == "mfma" else None,
+            "ms_per_step_if_every_executed_mfma_ran_at_ceiling": round(t_bound, 4),
+            "that_bound_over_step": round(t_bound / sum(per_pass), 4)}
     algb = algorithmic_bytes(w, w.total_tokens)
     out["hbm_algorithmic_GBs"] = round(algb / (sum(per_pass) * 1e-3) / 1e9, 1)
 

@@ -381,9 +381,9 @@ int psattn_probe_dq_atomics(const psattn_meta* meta, int32_t n_q_heads, int32_t 
  * issue 4 * iters (iters even) back-to-back v_mfma_f32_32x32x16_bf16 (32 768 FLOPs each per wave) on
  * register operands, with no memory traffic; sink is one device float that is never written.  FLOPs
  * launched = n_workgroups * 4 * 4 * iters * 32768.  random_operands = 0: one constant fragment per
- * operand side; 1: eight zero-mean, unit-scale pseudo-random fragments per side, a different pair
- * on every MFMA (the clock the device holds under matrix load depends on how much the data toggles);
- * 2: the eight-fragment register pattern of 1 holding the constant values of 0.
+ * operand side; 1: eight fragments per side with random sign and mantissa bits (magnitudes 0.5 to
+ * 2), a different pair on every MFMA (the clock the device holds under matrix load depends on how
+ * much the data toggles); 2: the eight-fragment register pattern of 1 holding the constants of 0.
  */
 int psattn_probe_mfma_peak(int32_t n_workgroups, int32_t iters, int32_t random_operands, float* sink,
                            void* hip_stream);

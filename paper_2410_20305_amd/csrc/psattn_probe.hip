@@ -42,37 +42,41 @@ __global__ __launch_bounds__(256) void psattn_dq_atomics_probe(DeviceMeta meta, 
 // independent v_mfma_f32_32x32x16_bf16 chains on register operands (no memory traffic at all).
 // With the clock the device holds under this load it is the ceiling any MFMA-bound kernel has.
 // MODE 0: one constant fragment per operand side (the data paths hardly toggle).
-// MODE 1: eight different fragments per side with values spread like the workloads' (zero-mean,
-// unit scale), a different pair on every MFMA: the clock the device then holds depends on the data.
+// MODE 1: eight different fragments per side holding pseudo-random values (random sign and mantissa,
+// magnitudes 0.5 to 2), a different pair on every MFMA: the clock the device holds depends on the data.
 // MODE 2: the register pattern of mode 1 with the constant values of mode 0 (tells the data apart
 // from the operand registers changing on every MFMA).
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 probe_bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float probe_f32x16;
 
-__device__ inline float probe_value(uint32_t key) {  // sum of four uniforms: zero mean, unit variance, bell-shaped
-    float v = 0.f;
-    for (int r = 0; r < 4; ++r) {
-        key = key * 1664525u + 1013904223u;
-        key ^= key >> 15;
-        key *= 2246822519u;
-        key ^= key >> 13;
-        v += static_cast<float>(key >> 8) * (1.0f / 16777216.0f) - 0.5f;
-    }
-    return v * 1.7320508f;
+// Two bf16 values in one register: random sign and mantissa, exponent 126 or 127 (magnitudes 0.5 to 2, zero mean)
+__device__ inline uint32_t probe_pair(uint32_t key) {
+    key = key * 1664525u + 1013904223u;
+    key ^= key >> 15;
+    key *= 2246822519u;
+    key ^= key >> 13;
+    return 0x3F003F00u | (key & 0x80FF80FFu);
 }
 
 template <int MODE>
 __global__ __launch_bounds__(256) void psattn_mfma_peak_probe(int iters, float* sink) {
     constexpr int F = MODE ? 8 : 1;
     constexpr bool RANDOM = MODE == 1;
+    union Frag { probe_bf16x8 v; uint32_t u[4]; };
+    Frag fa[F], fb[F];
     probe_bf16x8 a[F], b[F];
-    for (int f = 0; f < F; ++f)
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t key = ((blockIdx.x * 256u + threadIdx.x) * 8u + f) * 16u + j;
-            a[f][j] = static_cast<__bf16>(RANDOM ? probe_value(2u * key) : 1.0f + threadIdx.x * 1e-3f);
-            b[f][j] = static_cast<__bf16>(RANDOM ? probe_value(2u * key + 1u) : 0.5f);
+    const uint32_t lane_key = (blockIdx.x * 256u + threadIdx.x) * 64u;
+#pragma unroll
+    for (int f = 0; f < F; ++f) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            fa[f].u[j] = RANDOM ? probe_pair(lane_key + 8 * f + 2 * j) : 0x3F803F80u;      // constant: 1.0
+            fb[f].u[j] = RANDOM ? probe_pair(lane_key + 8 * f + 2 * j + 1) : 0x3F003F00u;  // constant: 0.5
         }
-    for (int f = 0; f < F; ++f) asm volatile("" : "+v"(a[f]), "+v"(b[f]));  // every fragment in registers of its own
+        a[f] = fa[f].v;
+        b[f] = fb[f].v;
+        asm volatile("" : "+v"(a[f]), "+v"(b[f]));  // every fragment in registers of its own
+    }
     probe_f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
     for (int i = 0; i < iters; i += 2) {  // eight MFMAs per turn; `iters` is even
         c0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], b[0], c0, 0, 0, 0);
