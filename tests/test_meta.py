@@ -129,6 +129,18 @@ def test_meta_errors():
     assert lib.psattn_strerror(-2).decode().startswith("samples")
 
 
+def test_probe_entry_points_validate_before_touching_a_device():
+    lib = ps.load_library()
+    one = ctypes.c_void_p(8)  # never dereferenced: every call below is rejected on its arguments
+    assert lib.psattn_probe_mfma_peak(0, 2, 0, one, None) == -1      # no workgroups
+    assert lib.psattn_probe_mfma_peak(4, 3, 0, one, None) == -1      # odd round count
+    assert lib.psattn_probe_mfma_peak(4, 2, 3, one, None) == -1      # unknown operand pattern
+    assert lib.psattn_probe_mfma_peak(4, 2, 1, None, None) == -1     # no sink
+    m = ps.psattn_build_meta([0], [4], [2], [2], 8, host_only=True)
+    assert lib.psattn_probe_dq_atomics(m.handle, 4, 3, one, 0, None) == -1   # heads do not divide
+    assert lib.psattn_probe_dq_atomics(m.handle, 4, 2, one, 0, None) == -7   # host-only meta
+
+
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "psattn.h")).read()
     declared = set(re.findall(r"\b(psattn_[a-z_]+)\s*\(", header))
