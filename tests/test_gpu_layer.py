@@ -59,3 +59,44 @@ def test_layer_forward_backward(case):
     layer.free()
     rope.free()
     meta.free()
+
+
+def test_layer_bench_shape():
+    """The shape and the smallest grid point `bench.py --layer` times: hidden 4096, 32 q / 8 kv heads of 128, four
+    equal samples of prompt 1024 and two completions of 128, theta 10 000, weights and activations drawn on the
+    device as the benchmark draws them; every output against the oracle."""
+    import torch
+    from gpu_util import rel_l2, to_np
+    from paper_2410_20305_amd.layer import Layer
+    hidden, Hq, Hkv, d, theta = 4096, 32, 8, 128, 10000.0
+    w = W.custom_workload([(1024, 128, 128)] * 4, hq=Hq, hkv=Hkv, d=d, dtype="bf16", seed=1152, name="layer")
+    T = w.total_tokens
+    g = torch.Generator(device="cuda")
+    g.manual_seed(3)
+    rnd = lambda *shape, s=1.0: (torch.randn(shape, generator=g, device="cuda", dtype=torch.float32) * s).to(torch.bfloat16)
+    Wq, Wk, Wv = rnd(Hq * d, hidden, s=hidden ** -0.5), rnd(Hkv * d, hidden, s=hidden ** -0.5), rnd(Hkv * d, hidden, s=hidden ** -0.5)
+    Wo = rnd(hidden, Hq * d, s=(Hq * d) ** -0.5)
+    X, dY = rnd(T, hidden), rnd(T, hidden)
+    meta = ps.psattn_build_meta(w.offset, w.prefix_len, w.chosen_len, w.rejected_len, T)
+    rope = ps.Rope(d, theta, 32768)
+    layer = Layer(hidden, Hq, Hkv, d)
+    ws = torch.empty(layer.workspace_bytes(meta), dtype=torch.uint8, device="cuda")
+    Y = layer.forward(meta, rope, w.scale, X, Wq, Wk, Wv, Wo, ws)
+    grads = layer.backward(meta, rope, w.scale, X, Wq, Wk, Wv, Wo, dY, ws)
+    torch.cuda.synchronize()
+    ptr = 2 * np.arange(w.n_samples + 1)
+    rl = np.stack([w.chosen_len, w.rejected_len], axis=1).reshape(-1)
+    D, B = orc.branch_arrays(w.offset, w.prefix_len, ptr, rl, T)
+    host = lambda t: t.float().cpu().numpy()
+    bf = lambda x: W.bf16_round(x.astype(np.float32))
+    ref = orc.layer_backward(host(X), host(Wq), host(Wk), host(Wv), host(Wo), host(dY), w.scale, theta, D, B,
+                             lambda *a: orc.dense_branch_mask(D, B, *a), Hq, Hkv, round_act=lambda x: bf(x).astype(np.float64))
+    got = dict(Y=to_np(Y), dX=to_np(grads[0]), dWq=to_np(grads[1]), dWk=to_np(grads[2]), dWv=to_np(grads[3]), dWo=to_np(grads[4]))
+    for name in ("Y", "dX", "dWq", "dWk", "dWv", "dWo"):
+        assert np.all(np.isfinite(got[name])), name
+        e = rel_l2(got[name], ref[name])
+        assert e <= 2e-2, (name, e)
+    layer.free()
+    rope.free()
+    meta.free()
+

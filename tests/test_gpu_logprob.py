@@ -56,6 +56,48 @@ def test_logprob_forward_backward(case, dtype):
     plan.free()
 
 
+@pytest.mark.parametrize("sample", [0, 9])
+def test_logprob_config5_vocab32000_sampled(sample):
+    """Full size, the launch configuration bench.py times as `logprob_head`: config 5's sample table, bf16
+    logits [65 536, 32 000] drawn on the device, both responses of one sample against the oracle.  A response's
+    log-probability and the gradient rows of its sample depend on that sample's rows only, so the oracle runs
+    on those rows (read back from the device) as a one-sample problem."""
+    import torch
+    w = W.make_workload("cfg5")
+    T, V = w.total_tokens, 32000
+    ptr = 2 * np.arange(w.n_samples + 1)
+    rl = np.stack([w.chosen_len, w.rejected_len], axis=1).reshape(-1)
+    plan = ps.LogprobPlan(w.offset, w.prefix_len, ptr, rl, T)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(3050)
+    lg = torch.empty((T, V), dtype=torch.bfloat16, device="cuda")
+    for t0 in range(0, T, 8192):   # in pieces: the fp32 draw of the whole buffer would be 8 GB
+        lg[t0:t0 + 8192] = (torch.randn((min(8192, T - t0), V), generator=gen, device="cuda") * 3).to(torch.bfloat16)
+    tid = torch.randint(0, V, (T,), generator=gen, device="cuda", dtype=torch.int32)
+    d_logp = torch.randn(len(rl), generator=gen, device="cuda")
+    row_lse, logp = ps.psattn_logprob_fwd(plan, lg, tid)
+    dlog = torch.full_like(lg, float("nan"))
+    ps.psattn_logprob_bwd(plan, lg, tid, row_lse, d_logp, dlogits=dlog)
+    torch.cuda.synchronize()
+    o, p, c, r = (int(x[sample]) for x in (w.offset, w.prefix_len, w.chosen_len, w.rejected_len))
+    n = p + c + r
+    sub_logits = lg[o:o + n].float().cpu().numpy()
+    sub_ids = tid[o:o + n].cpu().numpy()
+    sub_d = d_logp[2 * sample:2 * sample + 2].cpu().numpy().astype(np.float64)
+    ref = orc.response_logprobs(sub_logits, sub_ids, [0], [p], [0, 2], [c, r])
+    got = logp[2 * sample:2 * sample + 2].cpu().numpy().astype(np.float64)
+    # sums of up to a thousand fp32 terms of magnitude ~10: 1e-4 relative to the sum
+    assert np.abs(got - ref).max() <= 1e-4 * max(1.0, float(np.abs(ref).max())), (got, ref)
+    gref = orc.response_logprobs_grad(sub_logits, sub_ids, [0], [p], [0, 2], [c, r], sub_d)
+    ggot = dlog[o:o + n].float().cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(ggot))
+    silent = np.abs(gref).sum(axis=1) == 0
+    assert np.all(ggot[silent] == 0)
+    excess = float((np.abs(ggot - gref) - (2.0 ** -8 * np.abs(gref) + 1e-6)).max())
+    assert excess <= 0, excess
+    plan.free()
+
+
 def test_dpo_loss_matches_oracle():
     import torch
     rng = np.random.default_rng(302)

@@ -92,6 +92,52 @@ def test_rope_multi_response_and_large_theta():
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("sample,kv_group", [(2, 0), (4, 7)])
+def test_rope_config5_sampled(sample, kv_group):
+    """Full size, the launch configuration bench.py times as `rope_fused` (config 5, theta 500 000): one
+    sample x one kv-group (its 8 q-heads) against the oracle.  Position ids restart in every sample, so the
+    sample taken alone at offset 0 is the same problem; the oracle runs on that slice."""
+    import torch
+    from gpu_util import BF16_LSE_TOL, check_grad, check_o, dq_delta_floor, to_dev
+    w = W.make_workload("cfg5")
+    tens = W.make_tensors(w)
+    theta, d, T = 500000.0, w.head_dim, w.total_tokens
+    G = w.n_q_heads // w.n_kv_heads
+    meta = ps.psattn_build_meta(w.offset, w.prefix_len, w.chosen_len, w.rejected_len, T)
+    rope = ps.Rope(d, theta, meta.positions()[1])
+    Q, K, V, dO = (to_dev(tens[n], "bf16") for n in ("Q", "K", "V", "dO"))
+    nan = lambda x: torch.full_like(x, float("nan"))
+    O, Qr, Kr = nan(Q), nan(Q), nan(K)
+    LSE = torch.full((w.n_q_heads, T), float("nan"), dtype=torch.float32, device="cuda")
+    ps.psattn_fwd_rope(meta, rope, Q, K, V, w.scale, O=O, LSE=LSE, Qr=Qr, Kr=Kr)
+    dQ, dK, dV = nan(Q), nan(K), nan(K)
+    ps.psattn_bwd_rope(meta, rope, Qr, Kr, V, O, dO, LSE, w.scale, dQ=dQ, dK=dK, dV=dV)
+    torch.cuda.synchronize()
+    o, p, c, r = (int(x[sample]) for x in (w.offset, w.prefix_len, w.chosen_len, w.rejected_len))
+    n = p + c + r
+    heads = slice(kv_group * G, (kv_group + 1) * G)
+    np64 = lambda t: t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+    out = dict(O=np64(O[o:o + n, heads]), LSE=np64(LSE[heads, o:o + n]), dQ=np64(dQ[o:o + n, heads]),
+               dK=np64(dK[o:o + n, kv_group:kv_group + 1]), dV=np64(dV[o:o + n, kv_group:kv_group + 1]))
+    for v in out.values():
+        assert np.all(np.isfinite(v))
+    sub = {"Q": tens["Q"][o:o + n, heads], "dO": tens["dO"][o:o + n, heads],
+           "K": tens["K"][o:o + n, kv_group:kv_group + 1], "V": tens["V"][o:o + n, kv_group:kv_group + 1]}
+    D, B = orc.branch_arrays([0], [p], [0, 2], [c, r], n)
+    rnd = lambda x: W.bf16_round(x.astype(np.float32)).astype(np.float64)
+    ref = orc.backward_rope(sub["Q"], sub["K"], sub["V"], sub["dO"], w.scale, theta, D, B,
+                            lambda *a: orc.dense_branch_mask(D, B, *a), round_operands=rnd)
+    what = "rope cfg5 sample %d kv-group %d" % (sample, kv_group)
+    check_o(out["O"], ref["O"], what, tok0=o)
+    assert np.abs(out["LSE"] - ref["LSE"]).max() <= BF16_LSE_TOL
+    check_grad(out["dQ"], ref["dQ"], "dQ", what, dq_delta_floor(sub["dO"], ref["O"], sub["K"], w.scale))
+    for name in ("dK", "dV"):
+        check_grad(out[name], ref[name], name, what)
+    rope.free()
+    meta.free()
+
+
+@pytest.mark.gpu
 def test_rope_degenerate_buffers():
     """Nothing but padding, and a one-token sample: outputs are zeros / the token's own V row."""
     import torch
