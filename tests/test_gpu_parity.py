@@ -317,6 +317,22 @@ def test_bf16_ffd_packed_rows():
     compare_full(w, tens, out, "bf16", what="ffd packed rows")
 
 
+def test_config4_ffd_layout_sampled():
+    """Full size: config 4's 143 samples re-laid by the library's First-Fit-Decreasing packer into rows of 8192
+    (the layout bench.py times as `ffd_packing`), sampled against the oracle: the first and the last sample of the
+    buffer, two neighbours across a row boundary and two in the middle, first and last kv-group."""
+    w0 = W.make_workload("cfg4")
+    pk = ps.psattn_pack_ffd(w0.prefix_len, w0.chosen_len, w0.rejected_len, w0.row_len)
+    w = W.with_layout(w0, pk["offset"], pk["order"], pk["n_rows"] * w0.row_len, name="cfg4-ffd")
+    assert w.n_samples == w0.n_samples
+    tens = W.make_tensors(w)
+    out, _ = run_gpu(w, tens)
+    rows = (np.asarray(w.offset) // w0.row_len).tolist()
+    edge = next(i for i in range(1, w.n_samples) if rows[i] != rows[i - 1])   # first sample of the second row
+    compare_subset(w, tens, out, samples=[0, edge - 1, edge, w.n_samples // 2, w.n_samples // 2 + 1, w.n_samples - 1],
+                   kv_heads=[0, 7])
+
+
 def test_bf16_long_sample_tile_lists_beyond_two_batches():
     """One sample of 9 200 tokens: tile lists of up to 144 entries, so the kernels' 64-entry
     list windows are refilled twice (the five configurations stop at 128 entries); two q-heads
