@@ -317,6 +317,16 @@ def test_bf16_ffd_packed_rows():
     compare_full(w, tens, out, "bf16", what="ffd packed rows")
 
 
+def test_config2_paired_format_full():
+    """Full size: the unshared paired format of config 2 (16 plain-causal documents, 13 454 tokens), the layout whose
+    time bench.py reports as `paired_ms_per_step`, every output against the oracle."""
+    pw, _, _ = W.paired_workload(W.make_workload("cfg2"))
+    assert np.all(np.asarray(pw.chosen_len) == 0) and np.all(np.asarray(pw.rejected_len) == 0)
+    tens = W.make_tensors(pw)
+    out, _ = run_gpu(pw, tens)
+    compare_full(pw, tens, out, "bf16", what="cfg2 paired")
+
+
 def test_config4_ffd_layout_sampled():
     """Full size: config 4's 143 samples re-laid by the library's First-Fit-Decreasing packer into rows of 8192
     (the layout bench.py times as `ffd_packing`), sampled against the oracle: the first and the last sample of the
