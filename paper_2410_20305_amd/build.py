@@ -20,6 +20,9 @@ DEVICE_FLAGS = ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 # The dK/dV kernel manages the accumulation registers a[0:191] itself (see the head of its
 # source file); the compiler must not park spilled values there.
 SOURCE_FLAGS = {"psattn_mfma_dkdv.hip": ["-mllvm", "-amdgpu-spill-vgpr-to-agpr=0"],
+                # the forward takes its row maxima with fmaxf; without NaNs to honour that is one v_max3_f32 per
+                # three values (the kernels require finite inputs)
+                "psattn_mfma_fwd.hip": ["-fno-honor-nans"],
                 # the probe measures the hardware fp32 atomic add, not a compare-and-swap loop
                 "psattn_probe.hip": ["-munsafe-fp-atomics"]}
 

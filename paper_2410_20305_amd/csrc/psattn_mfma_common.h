@@ -146,14 +146,6 @@ __device__ __forceinline__ float keep_or_neg_inf(float x, uint32_t bits) {
     return __uint_as_float((__float_as_uint(x) & m) | (~m & 0xff800000u));
 }
 
-// max(a, b, c) in one instruction.  (fmaxf makes the compiler quiet possible signalling
-// NaNs with an extra v_max per operand; scores are never NaN.)
-__device__ __forceinline__ float max3(float a, float b, float c) {
-    float r;
-    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
-    return r;
-}
-
 __device__ inline f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }

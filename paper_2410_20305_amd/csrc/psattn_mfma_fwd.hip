@@ -5,6 +5,9 @@ namespace psattn {
 namespace {
 using namespace mma;
 
+// max(a, b, c); scores are never NaN (the inputs must be finite)
+__device__ __forceinline__ float fmax3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
+
 // ------------------------------------------------------------------ forward
 // grid: one workgroup per (q-tile of 128 queries, q-head); 4 waves x 32 queries.
 __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
@@ -141,25 +144,22 @@ __global__ __launch_bounds__(256, 2) void psattn_fwd_bf16_mfma(AttnArgs a) {
                 s[e >> 4][e & 15] = keep_or_neg_inf<e>(s[e >> 4][e & 15], bits);
             });
         }
-        // The maxima below are taken by inline assembly (max3), which the compiler does not treat as a
-        // vector-ALU reader of MFMA results when it places wait states, so the wait states between the
-        // last S MFMA and them are put here by hand (an MFMA of this shape needs up to 18 before the
-        // vector ALU may read its result; without them the maxima were seen to read scores of the
-        // previous tile now and then).  The statement names the scores as operands so that the maxima
-        // cannot be moved above it.
-        asm volatile("s_nop 15\n\ts_nop 3" : "+v"(s[0]), "+v"(s[1]));
+        // The maxima are ordinary compiled code (this file is built with -fno-honor-nans, so that
+        // fmaxf(fmaxf(a, b), c) becomes one v_max3_f32 without NaN-quieting instructions): the compiler
+        // sees a vector-ALU reader of MFMA results and places the wait states such a reader needs.  (An
+        // inline-assembly maximum is not seen as one, and then read scores of the previous tile now and then.)
         // four independent chains each for the maximum and (below) the sum
         float mxp[4];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mxp[r] = max3(s[0][r], s[1][r], s[0][r + 4]);
+        for (int r = 0; r < 4; ++r) mxp[r] = fmax3(s[0][r], s[1][r], s[0][r + 4]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mxp[r] = max3(mxp[r], s[1][r + 4], s[0][r + 8]);
+        for (int r = 0; r < 4; ++r) mxp[r] = fmax3(mxp[r], s[1][r + 4], s[0][r + 8]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mxp[r] = max3(mxp[r], s[1][r + 8], s[0][r + 12]);
+        for (int r = 0; r < 4; ++r) mxp[r] = fmax3(mxp[r], s[1][r + 8], s[0][r + 12]);
 #pragma unroll
-        for (int r = 0; r < 4; ++r) mxp[r] = max3(mxp[r], s[1][r + 12], mxp[r]);
-        float mx = max3(mxp[0], mxp[1], max3(mxp[2], mxp[3], mxp[3]));
-        mx = max3(mx, other_half(mx), mx);
+        for (int r = 0; r < 4; ++r) mxp[r] = fmax3(mxp[r], s[1][r + 12], mxp[r]);
+        float mx = fmax3(mxp[0], mxp[1], fmax3(mxp[2], mxp[3], mxp[3]));
+        mx = fmax3(mx, other_half(mx), mx);
         // Exact running maximum; O and l are rescaled only in tiles where some row's maximum
         // moves (wave ballot).  Letting the reference lag behind the maximum was measured
         // both ways: a fixed lag of 2^8 saves 5 % of this kernel but the largest probability of
