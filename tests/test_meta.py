@@ -116,6 +116,8 @@ def test_meta_errors():
     assert status([4, 0], [2, 2], [0, 0], [0, 0], 8) == -2      # unsorted
     assert status([0, 2], [2, 2], [1, 0], [0, 0], 8) == -2      # overlap
     assert status([0], [4], [4], [4], 8) == -3                  # beyond the buffer
+    # a grid whose tile index would not fit the 30 bits a list entry has for it: refused before anything is built
+    assert status([0], [4], [2], [2], 1 << 29, tile_q=1, tile_k=1, bwd_tile_q=1, bwd_tile_k=1) == -6
     lib = ps.load_library()
     assert lib.psattn_build_meta_host(1, None, None, None, None, 4, 0, 0, 0, 0,
                                       ctypes.byref(ctypes.c_void_p())) == -1
